@@ -1,0 +1,159 @@
+/*
+ * paro.h - C ABI of the MI355X (gfx950) PAROAttention hot path (arXiv 2506.16054).
+ *
+ * The path is the attention call of a visual diffusion transformer after each head's tokens
+ * have been reordered by pattern (paper Sec. 4):
+ *
+ *   paro_permute   (Q, K, V)        reorder tokens into one of the six (F,H,W) orders   Sec. 4.1
+ *   paro_quantize  (Q, K, V)        one symmetric scale per block of `block` tokens     Sec. 4.3 (1)
+ *   paro_mask_to_blocklist          static per-head bitmask -> compacted live-block list Sec. 4.2 (1),(2)
+ *   paro_sparse_attn                FlashAttention-style loop over live blocks only,
+ *                                   INT8 QK^T and INT8/INT4 PV with block-wise scales     Sec. 4.2 (2), 4.3
+ *   paro_unpermute (O)              put output rows back into the default order          Sec. 4.1
+ *
+ * Conventions
+ *   - Every function returns 0 (PARO_OK) or a negative paro_status.  Arguments are checked on
+ *     the host before anything is launched; on error nothing has been enqueued and
+ *     paro_last_error() (thread-local text) says which argument was rejected.
+ *   - Pointers are DEVICE pointers unless their name starts with `h_` (host).  The caller owns
+ *     every buffer; the library neither allocates nor frees device memory and never
+ *     synchronizes.  Device work is enqueued on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream) and the call returns immediately.
+ *   - Tensors are contiguous, row-major, in the stated shape.  perm_ids, masks and block lists
+ *     are per head and shared over the batch (the paper finds both prompt-invariant, Sec. 4.1/4.2).
+ *   - N = F*Hg*Wg + T_text tokens; k = ceil(N / block) blocks; Npad = k * block.  Reordered
+ *     tensors are padded to Npad rows (zero rows), so every block is whole in memory; padded
+ *     keys never receive probability mass and padded query rows are never stored by
+ *     paro_unpermute.
+ */
+#ifndef PARO_H
+#define PARO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum paro_status {
+    PARO_OK = 0,
+    PARO_EINVAL = -1,       /* null pointer, bad shape, id or enum out of range            */
+    PARO_EUNSUPPORTED = -2, /* valid request the kernels do not cover (see each function)  */
+    PARO_EHIP = -3          /* the HIP runtime refused the launch; text in paro_last_error */
+} paro_status;
+
+typedef enum paro_dtype { PARO_F32 = 0, PARO_BF16 = 1 } paro_dtype;
+
+/* Memory layout of a quantized (or re-laid-out) operand, per (batch, head):
+ *   PARO_ROWS  codes[n][c], n in [0,Npad), c in [0,d)                      - used for Q and K
+ *   PARO_VT    codes[blk][c][slot], blk in [0,k), slot in [0,block): the block is stored
+ *              transposed (channel-major) with the tokens of the block in "slot" order,
+ *              slot = paro_vt_slot(block, n - blk*block).  This is the order in which the PV
+ *              matrix instruction consumes the key dimension, so the kernel reads V with
+ *              16-byte loads and never transposes on chip.                - used for V
+ * For bits == 4, two codes share a byte.  PARO_ROWS: channel 2c in bits 0-3, 2c+1 in bits 4-7.
+ * PARO_VT: within each group of 8 consecutive slots, byte t (t = 0..3) holds slot 8g+t in
+ * bits 0-3 and slot 8g+4+t in bits 4-7 (two's complement nibbles in [-7, 7]).
+ */
+typedef enum paro_layout { PARO_ROWS = 0, PARO_VT = 1 } paro_layout;
+
+typedef struct paro_shape {
+    int32_t B;      /* batch                                        */
+    int32_t nh;     /* heads                                        */
+    int32_t d;      /* head dimension: 64 or 128                    */
+    int32_t F;      /* latent grid: frames                          */
+    int32_t Hg;     /* latent grid: height                          */
+    int32_t Wg;     /* latent grid: width                           */
+    int32_t T_text; /* text tokens appended after the image tokens  */
+    int32_t block;  /* block size for sparsity and quantization: 32 or 64 (paper: 64) */
+} paro_shape;
+
+/* ---- host-only helpers (no GPU needed) -------------------------------------------------- */
+
+int paro_version(void);
+const char* paro_strerror(int status);
+const char* paro_last_error(void);
+
+/* Shape arithmetic; return a negative status on an invalid shape. */
+int64_t paro_ntokens(const paro_shape* s); /* N    */
+int64_t paro_nblocks(const paro_shape* s); /* k    */
+int64_t paro_npad(const paro_shape* s);    /* Npad */
+
+/* Gather index of axis order `perm_id` (Sec. 4.1; the six orders of (F,H,W) numbered
+ * lexicographically over the letters FHW, slowest axis first: 0 FHW, 1 FWH, 2 HFW, 3 HWF,
+ * 4 WFH, 5 WHF).  h_idx[n'] = position in the default [F,H,W] order of the token that sits at
+ * n' after the reorder; text tokens map to themselves.  h_idx has N entries (host). */
+int paro_perm_index(const paro_shape* s, int perm_id, int32_t* h_idx);
+
+/* Slot of token `i` (0 <= i < block) inside a PARO_VT block; a bijection on [0, block).
+ * Returns a negative status for an unsupported block size or i out of range. */
+int paro_vt_slot(int block, int i);
+
+/* Bitmask -> compacted block list (Sec. 4.2: masks are stored as bitmasks, whole blocks are
+ * skipped).  h_bitmask: [nh][ceil(k*k/8)] bytes; bit (i*k + j) of a head, LSB first in each
+ * byte, says row block i attends column block j (coordinates of the REORDERED sequence).
+ * h_row_ptr: [nh][k+1] offsets into h_col_idx (one array for all heads; row (h,i) owns
+ * [h_row_ptr[h][i], h_row_ptr[h][i+1]) ); columns ascending within a row.  `cap` is the
+ * capacity of h_col_idx in entries; *nnz_out receives the number of live blocks.  If cap is
+ * too small the function returns PARO_EINVAL after writing *nnz_out, so a caller may size the
+ * array with a first call (h_col_idx may then be NULL with cap 0).  All pointers are host. */
+int paro_mask_to_blocklist(int nh, int k, const uint8_t* h_bitmask, int32_t* h_row_ptr,
+                           int32_t* h_col_idx, int64_t cap, int64_t* nnz_out);
+
+/* ---- device entry points ---------------------------------------------------------------- */
+
+/* Token reorder (Sec. 4.1): xp[b,h,n',:] = x[b,h,idx_h[n'],:], rows n' >= N of xp set to 0.
+ *   h_perm_ids  host, [nh], values 0..5
+ *   x           [B,nh,N,d]     dtype
+ *   xp          [B,nh,Npad,d]  dtype   (must not alias x) */
+int paro_permute(const paro_shape* s, paro_dtype dtype, const uint8_t* h_perm_ids, const void* x,
+                 void* xp, void* stream);
+
+/* Inverse reorder of the attention output (Sec. 4.1): o[b,h,idx_h[n'],:] = op[b,h,n',:], n' < N.
+ *   op [B,nh,Npad,d] dtype;  o [B,nh,N,d] dtype (must not alias op) */
+int paro_unpermute(const paro_shape* s, paro_dtype dtype, const uint8_t* h_perm_ids, const void* op,
+                   void* o, void* stream);
+
+/* Block-aligned symmetric quantizer (Sec. 4.3 (1)): for every (b, h, block) one group of
+ * `block` tokens x d channels: absmax over rows < N; scale = absmax / qmax in binary32
+ * (1.0 if absmax == 0); code = clamp(round_half_even(x / scale), -qmax, qmax) with a correctly
+ * rounded binary32 divide; rows >= N give code 0.  qmax = 127 (bits 8) or 7 (bits 4).
+ * bits == 16 is the unquantized mode: values are re-laid-out as bf16 without rounding beyond
+ * the bf16 cast (exact for PARO_BF16 input) and all scales are 1.
+ *   xp      [B,nh,Npad,d] dtype            (reordered, zero-padded input)
+ *   codes   bits 8 : int8  [B,nh,Npad,d]     (PARO_ROWS)  or [B,nh,k,d,block]    (PARO_VT)
+ *           bits 4 : bytes [B,nh,Npad,d/2]   (PARO_ROWS)  or [B,nh,k,d,block/2]  (PARO_VT)
+ *           bits 16: bf16  same index space as bits 8
+ *   scales  float32 [B,nh,k] */
+int paro_quantize(const paro_shape* s, paro_dtype dtype, int bits, paro_layout layout,
+                  const void* xp, void* codes, float* scales, void* stream);
+
+/* Block-sparse attention over the live blocks of each row block (Sec. 4.2 (2), Sec. 4.3):
+ * for row block i of head h, visiting its live column blocks j in the order of the list
+ * (ascending), with running row maximum m, denominator l and accumulator acc:
+ *     X   = (Qc_i Kc_j^T) * sq[i] * sk[j] / sqrt(d)      integer product, i32 accumulate;
+ *                                                         keys >= N get -inf
+ *     m'  = max(m, rowmax X);  Pt = exp(X - m');  l = l*exp(m-m') + rowsum(Pt)
+ *     sP  = max(Pt over the block x block tile, rows < N) / qmax_P;  Pc = round_half_even(Pt / sP)
+ *     acc = acc*exp(m-m') + sP * sv[j] * (Pc Vc_j)       integer product, i32 accumulate
+ * and finally op_i = acc / l (zeros if the row block has no live block).
+ *   bits_qk  8 (int8 codes, PARO_ROWS) or 16 (bf16 values from paro_quantize(bits 16), PARO_ROWS)
+ *   bits_pv  8 or 4 (codes, PARO_VT, P quantized to the same width) or 16 (bf16, PARO_VT, P kept
+ *            in bf16);  supported pairs: (8,8), (8,4), (16,16)
+ *   q,k      [B,nh,Npad,d] as produced by paro_quantize(..., PARO_ROWS, ...)
+ *   v        as produced by paro_quantize(..., PARO_VT, ...)
+ *   sq,sk,sv float32 [B,nh,k] (ignored, may be NULL, when the operand is 16-bit)
+ *   row_ptr  int32 [nh][k+1], col_idx int32 [nnz]: DEVICE copies of the block list; entries
+ *            outside [0,nnz] / [0,k) are clamped, so a corrupt list cannot address outside the
+ *            operands (the result is then meaningless but the call is memory-safe)
+ *   op       [B,nh,Npad,d] out_dtype; rows >= N are written as zeros */
+int paro_sparse_attn(const paro_shape* s, int bits_qk, int bits_pv, const void* q, const float* sq,
+                     const void* k, const float* sk, const void* v, const float* sv,
+                     const int32_t* row_ptr, const int32_t* col_idx, int64_t nnz,
+                     paro_dtype out_dtype, void* op, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PARO_H */

@@ -1,0 +1,233 @@
+"""Thin ctypes binding over libparo.so: same names as the C ABI (include/paro.h), argument
+marshalling only.  Device tensors are torch tensors (device memory + the current HIP stream);
+every step of the path runs inside the library's kernels.
+
+The library is loaded on first use and the binding fails loudly if it has not been built
+(``python -m paper_2506_16054_amd.build``): there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+
+PARO_OK = 0
+PARO_EINVAL = -1
+PARO_EUNSUPPORTED = -2
+PARO_EHIP = -3
+PARO_F32 = 0
+PARO_BF16 = 1
+PARO_ROWS = 0
+PARO_VT = 1
+
+LIBPATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libparo.so")
+
+EXPORTS = (
+    "paro_version", "paro_strerror", "paro_last_error", "paro_ntokens", "paro_nblocks", "paro_npad",
+    "paro_perm_index", "paro_vt_slot", "paro_mask_to_blocklist", "paro_permute", "paro_unpermute",
+    "paro_quantize", "paro_sparse_attn",
+)
+
+
+class ParoError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("paro status %d: %s" % (status, message))
+        self.status = status
+
+
+class paro_shape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "nh", "d", "F", "Hg", "Wg", "T_text", "block")]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIBPATH):
+            raise ParoError(PARO_EHIP, "%s is missing: build it with `python -m paper_2506_16054_amd.build`" % LIBPATH)
+        L = ctypes.CDLL(LIBPATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+        sp = ctypes.POINTER(paro_shape)
+        L.paro_version.restype = i32
+        L.paro_strerror.restype = ctypes.c_char_p
+        L.paro_strerror.argtypes = [i32]
+        L.paro_last_error.restype = ctypes.c_char_p
+        for f in (L.paro_ntokens, L.paro_nblocks, L.paro_npad):
+            f.restype = i64
+            f.argtypes = [sp]
+        L.paro_perm_index.argtypes = [sp, i32, vp]
+        L.paro_vt_slot.argtypes = [i32, i32]
+        L.paro_mask_to_blocklist.argtypes = [i32, i32, vp, vp, vp, i64, ctypes.POINTER(i64)]
+        L.paro_permute.argtypes = [sp, i32, vp, vp, vp, vp]
+        L.paro_unpermute.argtypes = [sp, i32, vp, vp, vp, vp]
+        L.paro_quantize.argtypes = [sp, i32, i32, i32, vp, vp, vp, vp]
+        L.paro_sparse_attn.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != PARO_OK:
+        raise ParoError(status, lib().paro_last_error().decode() or lib().paro_strerror(status).decode())
+
+
+def make_shape(B: int, nh: int, d: int, F: int, Hg: int, Wg: int, T_text: int, block: int) -> paro_shape:
+    return paro_shape(B, nh, d, F, Hg, Wg, T_text, block)
+
+
+def shape_of(w) -> paro_shape:
+    """paro_shape of a workloads.Workload."""
+    return paro_shape(w.B, w.nh, w.d, w.F, w.Hg, w.Wg, w.T_text, w.block)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dtype_code(t) -> int:
+    import torch
+
+    if t.dtype == torch.float32:
+        return PARO_F32
+    if t.dtype == torch.bfloat16:
+        return PARO_BF16
+    raise ParoError(PARO_EINVAL, "tensor dtype %s is neither float32 nor bfloat16" % t.dtype)
+
+
+def _require(t, name: str, shape=None, dtype=None):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ParoError(PARO_EINVAL, "%s must be a contiguous device tensor" % name)
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ParoError(PARO_EINVAL, "%s has shape %s, expected %s" % (name, tuple(t.shape), tuple(shape)))
+    if dtype is not None and t.dtype != dtype:
+        raise ParoError(PARO_EINVAL, "%s has dtype %s, expected %s" % (name, t.dtype, dtype))
+
+
+# ---------------------------------------------------------------------------------------------
+# host-only calls
+# ---------------------------------------------------------------------------------------------
+def paro_version() -> int:
+    return lib().paro_version()
+
+
+def paro_ntokens(s: paro_shape) -> int:
+    n = lib().paro_ntokens(ctypes.byref(s))
+    if n < 0:
+        _check(int(n))
+    return int(n)
+
+
+def paro_nblocks(s: paro_shape) -> int:
+    n = lib().paro_nblocks(ctypes.byref(s))
+    if n < 0:
+        _check(int(n))
+    return int(n)
+
+
+def paro_npad(s: paro_shape) -> int:
+    n = lib().paro_npad(ctypes.byref(s))
+    if n < 0:
+        _check(int(n))
+    return int(n)
+
+
+def paro_perm_index(s: paro_shape, perm_id: int) -> np.ndarray:
+    n = paro_ntokens(s)
+    idx = np.empty(n, np.int32)
+    _check(lib().paro_perm_index(ctypes.byref(s), int(perm_id), idx.ctypes.data))
+    return idx
+
+
+def paro_vt_slot(block: int, i: int) -> int:
+    r = lib().paro_vt_slot(int(block), int(i))
+    if r < 0:
+        _check(r)
+    return r
+
+
+def paro_mask_to_blocklist(nh: int, k: int, bitmask: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """bitmask uint8 [nh, ceil(k*k/8)] -> (row_ptr int32 [nh, k+1], col_idx int32 [nnz]), host arrays."""
+    bm = np.ascontiguousarray(bitmask, dtype=np.uint8)
+    if bm.shape != (nh, (k * k + 7) // 8):
+        raise ParoError(PARO_EINVAL, "bitmask has shape %s, expected %s" % (bm.shape, (nh, (k * k + 7) // 8)))
+    row_ptr = np.empty((nh, k + 1), np.int32)
+    nnz = ctypes.c_int64(0)
+    st = lib().paro_mask_to_blocklist(nh, k, bm.ctypes.data, row_ptr.ctypes.data, None, 0, ctypes.byref(nnz))
+    if st != PARO_OK and nnz.value == 0:
+        _check(st)
+    col_idx = np.empty(max(nnz.value, 1), np.int32)
+    _check(lib().paro_mask_to_blocklist(nh, k, bm.ctypes.data, row_ptr.ctypes.data, col_idx.ctypes.data, col_idx.size, ctypes.byref(nnz)))
+    return row_ptr, col_idx[: nnz.value]
+
+
+# ---------------------------------------------------------------------------------------------
+# device calls (torch tensors on the GPU; enqueued on torch's current stream)
+# ---------------------------------------------------------------------------------------------
+def _perm_bytes(s: paro_shape, perm_ids) -> np.ndarray:
+    p = np.ascontiguousarray(perm_ids, dtype=np.uint8)
+    if p.shape != (s.nh,):
+        raise ParoError(PARO_EINVAL, "perm_ids has shape %s, expected (%d,)" % (p.shape, s.nh))
+    return p
+
+
+def paro_permute(s: paro_shape, perm_ids, x, xp) -> None:
+    n, npad = paro_ntokens(s), paro_npad(s)
+    _require(x, "x", (s.B, s.nh, n, s.d))
+    _require(xp, "xp", (s.B, s.nh, npad, s.d), x.dtype)
+    p = _perm_bytes(s, perm_ids)
+    _check(lib().paro_permute(ctypes.byref(s), _dtype_code(x), p.ctypes.data, _ptr(x), _ptr(xp), _stream()))
+
+
+def paro_unpermute(s: paro_shape, perm_ids, op, o) -> None:
+    n, npad = paro_ntokens(s), paro_npad(s)
+    _require(op, "op", (s.B, s.nh, npad, s.d))
+    _require(o, "o", (s.B, s.nh, n, s.d), op.dtype)
+    p = _perm_bytes(s, perm_ids)
+    _check(lib().paro_unpermute(ctypes.byref(s), _dtype_code(op), p.ctypes.data, _ptr(op), _ptr(o), _stream()))
+
+
+def codes_shape(s: paro_shape, bits: int, layout: int) -> Tuple[int, ...]:
+    """Shape of the `codes` tensor of paro_quantize (int8 bytes for bits 8/4, bf16 for bits 16)."""
+    k, npad = paro_nblocks(s), paro_npad(s)
+    pack = 2 if bits == 4 else 1
+    if layout == PARO_ROWS:
+        return (s.B, s.nh, npad, s.d // pack)
+    return (s.B, s.nh, k, s.d, s.block // pack)
+
+
+def paro_quantize(s: paro_shape, bits: int, layout: int, xp, codes, scales) -> None:
+    import torch
+
+    _require(xp, "xp", (s.B, s.nh, paro_npad(s), s.d))
+    _require(codes, "codes", codes_shape(s, bits, layout), torch.bfloat16 if bits == 16 else torch.int8)
+    _require(scales, "scales", (s.B, s.nh, paro_nblocks(s)), torch.float32)
+    _check(lib().paro_quantize(ctypes.byref(s), _dtype_code(xp), int(bits), int(layout), _ptr(xp), _ptr(codes), _ptr(scales), _stream()))
+
+
+def paro_sparse_attn(s: paro_shape, bits_qk: int, bits_pv: int, q, sq, k, sk, v, sv, row_ptr, col_idx, op) -> None:
+    import torch
+
+    kb, npad = paro_nblocks(s), paro_npad(s)
+    _require(q, "q", codes_shape(s, bits_qk, PARO_ROWS))
+    _require(k, "k", codes_shape(s, bits_qk, PARO_ROWS))
+    _require(v, "v", codes_shape(s, bits_pv, PARO_VT))
+    for name, t in (("sq", sq), ("sk", sk), ("sv", sv)):
+        if t is not None:
+            _require(t, name, (s.B, s.nh, kb), torch.float32)
+    _require(row_ptr, "row_ptr", (s.nh, kb + 1), torch.int32)
+    _require(col_idx, "col_idx", None, torch.int32)
+    _require(op, "op", (s.B, s.nh, npad, s.d))
+    _check(lib().paro_sparse_attn(ctypes.byref(s), int(bits_qk), int(bits_pv), _ptr(q), _ptr(sq), _ptr(k), _ptr(sk), _ptr(v),
+                                  _ptr(sv), _ptr(row_ptr), _ptr(col_idx) if col_idx.numel() else None, int(col_idx.numel()),
+                                  _dtype_code(op), _ptr(op), _stream()))

@@ -1,0 +1,138 @@
+// Host-only part of libparo: status text, shape arithmetic, the gather index of an axis order
+// (paper Sec. 4.1), the PARO_VT slot map and the bitmask -> block-list conversion (Sec. 4.2).
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "common.h"
+
+namespace paro {
+
+static thread_local char g_last_error[512] = "";
+
+int fail(int status, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_last_error, sizeof(g_last_error), fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+int check_shape(const paro_shape* s, int64_t* n_tokens, int64_t* k_blocks) {
+    if (!s) return fail(PARO_EINVAL, "shape is NULL");
+    if (s->B < 1 || s->nh < 1) return fail(PARO_EINVAL, "B=%d nh=%d must be >= 1", s->B, s->nh);
+    if ((int64_t)s->B * s->nh > 65535) return fail(PARO_EUNSUPPORTED, "B*nh=%lld exceeds 65535", (long long)s->B * s->nh);
+    if (s->nh > kMaxHeads) return fail(PARO_EUNSUPPORTED, "nh=%d exceeds %d", s->nh, kMaxHeads);
+    if (s->d != 64 && s->d != 128) return fail(PARO_EUNSUPPORTED, "d=%d: only 64 and 128 are built", s->d);
+    if (s->block != 32 && s->block != 64)
+        return fail(PARO_EUNSUPPORTED, "block=%d: only 32 and 64 are built", s->block);
+    if (s->F < 1 || s->Hg < 1 || s->Wg < 1 || s->T_text < 0)
+        return fail(PARO_EINVAL, "grid %dx%dx%d (+%d text) is not a valid token grid", s->F, s->Hg, s->Wg, s->T_text);
+    const int64_t n = (int64_t)s->F * s->Hg * s->Wg + s->T_text;
+    const int64_t k = (n + s->block - 1) / s->block;
+    if (n > (1 << 24)) return fail(PARO_EUNSUPPORTED, "N=%lld exceeds 2^24 tokens", (long long)n);
+    if ((int64_t)s->B * s->nh * k > (int64_t)1 << 30)
+        return fail(PARO_EUNSUPPORTED, "B*nh*k=%lld exceeds the launch limit", (long long)((int64_t)s->B * s->nh * k));
+    if (n_tokens) *n_tokens = n;
+    if (k_blocks) *k_blocks = k;
+    return PARO_OK;
+}
+
+int check_launch(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(PARO_EHIP, "%s: %s", what, hipGetErrorString(e));
+    return PARO_OK;
+}
+
+}  // namespace paro
+
+using namespace paro;
+
+extern "C" {
+
+int paro_version(void) { return 1; }
+
+const char* paro_strerror(int status) {
+    switch (status) {
+        case PARO_OK: return "ok";
+        case PARO_EINVAL: return "invalid argument";
+        case PARO_EUNSUPPORTED: return "unsupported configuration";
+        case PARO_EHIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+const char* paro_last_error(void) { return g_last_error; }
+
+int64_t paro_ntokens(const paro_shape* s) {
+    int64_t n, k;
+    int st = check_shape(s, &n, &k);
+    return st ? st : n;
+}
+
+int64_t paro_nblocks(const paro_shape* s) {
+    int64_t n, k;
+    int st = check_shape(s, &n, &k);
+    return st ? st : k;
+}
+
+int64_t paro_npad(const paro_shape* s) {
+    int64_t n, k;
+    int st = check_shape(s, &n, &k);
+    return st ? st : k * s->block;
+}
+
+int paro_perm_index(const paro_shape* s, int perm_id, int32_t* h_idx) {
+    int64_t n, k;
+    if (int st = check_shape(s, &n, &k)) return st;
+    if (perm_id < 0 || perm_id > 5) return fail(PARO_EINVAL, "perm_id=%d not in 0..5", perm_id);
+    if (!h_idx) return fail(PARO_EINVAL, "h_idx is NULL");
+    const AxisOrder o = axis_order(perm_id);
+    const int dims[3] = {s->F, s->Hg, s->Wg};
+    const int stride[3] = {s->Hg * s->Wg, s->Wg, 1};
+    // Walk the reordered sequence: the three loop counters are the coordinates along the
+    // slowest, middle and fastest axis of the chosen order.
+    int64_t pos = 0;
+    for (int c0 = 0; c0 < dims[o.a[0]]; ++c0)
+        for (int c1 = 0; c1 < dims[o.a[1]]; ++c1)
+            for (int c2 = 0; c2 < dims[o.a[2]]; ++c2)
+                h_idx[pos++] = c0 * stride[o.a[0]] + c1 * stride[o.a[1]] + c2 * stride[o.a[2]];
+    for (; pos < n; ++pos) h_idx[pos] = (int32_t)pos;  // text tokens keep their place
+    return PARO_OK;
+}
+
+int paro_vt_slot(int block, int i) {
+    if (block != 32 && block != 64) return fail(PARO_EUNSUPPORTED, "block=%d: only 32 and 64 are built", block);
+    if (i < 0 || i >= block) return fail(PARO_EINVAL, "token %d outside a block of %d", i, block);
+    return vt_slot(i);
+}
+
+int paro_mask_to_blocklist(int nh, int k, const uint8_t* h_bitmask, int32_t* h_row_ptr, int32_t* h_col_idx,
+                           int64_t cap, int64_t* nnz_out) {
+    if (nh < 1 || k < 1) return fail(PARO_EINVAL, "nh=%d k=%d must be >= 1", nh, k);
+    if (!h_bitmask || !h_row_ptr || !nnz_out) return fail(PARO_EINVAL, "h_bitmask, h_row_ptr and nnz_out must not be NULL");
+    if (cap < 0 || (cap > 0 && !h_col_idx)) return fail(PARO_EINVAL, "h_col_idx is NULL but cap=%lld", (long long)cap);
+    const int64_t bits = (int64_t)k * k;
+    const int64_t bytes_per_head = (bits + 7) / 8;
+    if ((int64_t)nh * bits >= ((int64_t)1 << 31)) return fail(PARO_EUNSUPPORTED, "block list offsets would overflow int32");
+    int64_t nnz = 0;
+    for (int h = 0; h < nh; ++h) {
+        const uint8_t* m = h_bitmask + (int64_t)h * bytes_per_head;
+        for (int i = 0; i < k; ++i) {
+            h_row_ptr[(int64_t)h * (k + 1) + i] = (int32_t)nnz;
+            for (int j = 0; j < k; ++j) {
+                const int64_t bit = (int64_t)i * k + j;
+                if ((m[bit >> 3] >> (bit & 7)) & 1) {
+                    if (nnz < cap) h_col_idx[nnz] = j;
+                    ++nnz;
+                }
+            }
+        }
+        h_row_ptr[(int64_t)h * (k + 1) + k] = (int32_t)nnz;
+    }
+    *nnz_out = nnz;
+    if (nnz > cap) return fail(PARO_EINVAL, "h_col_idx holds %lld entries but the mask has %lld live blocks", (long long)cap, (long long)nnz);
+    return PARO_OK;
+}
+
+}  // extern "C"

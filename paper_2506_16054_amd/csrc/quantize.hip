@@ -1,0 +1,202 @@
+// Block-aligned symmetric quantizer (paper Sec. 4.3 (1)): one scale per group of `block` tokens
+// x d channels of one head, aligned with the attention block.  Bound by HBM bandwidth: every
+// element is read once (2 or 4 bytes) and written once (0.5, 1 or 2 bytes).
+//
+// One workgroup of 256 threads owns one group.  The tile stays in registers between the absmax
+// pass and the code pass, so HBM is touched exactly once in each direction.  The absmax is
+// reduced inside each wavefront with cross-lane shuffles and across the four wavefronts through
+// LDS.  For the PARO_VT layout the codes are transposed through LDS so that the global stores
+// stay 16 bytes per lane and contiguous.
+#include <hip/hip_bf16.h>
+
+#include "common.h"
+
+namespace paro {
+
+template <typename T>
+__device__ inline void load8(const T* p, float (&x)[8]);
+
+template <>
+__device__ inline void load8<float>(const float* p, float (&x)[8]) {
+    const float4 a = ((const float4*)p)[0];
+    const float4 b = ((const float4*)p)[1];
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+
+template <>
+__device__ inline void load8<uint16_t>(const uint16_t* p, float (&x)[8]) {  // bf16 bit patterns
+    const uint4 a = *(const uint4*)p;
+    const unsigned w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[2 * i] = __uint_as_float(w[i] << 16);
+        x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+
+__device__ inline unsigned f32_to_bf16_bits(float f) {  // round to nearest even
+    const unsigned u = __float_as_uint(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+__device__ inline float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+    return v;
+}
+
+template <typename InT, int BLK, int D, int BITS, int LAYOUT>
+__global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ xp, uint8_t* __restrict__ codes,
+                                                       float* __restrict__ scales, int n_tokens, int kblocks) {
+    constexpr int ELEMS = BLK * D;
+    constexpr int CHUNKS = ELEMS / 8;  // 8 consecutive channels of one token per chunk
+    constexpr int IT = (CHUNKS + 255) / 256;
+    constexpr int OUT_BYTES = ELEMS * BITS / 8;
+    constexpr float QMAX = BITS == 4 ? 7.0f : 127.0f;
+    // LDS staging of the transposed tile: bytes for 8- and 4-bit codes, 16-bit words for bf16.
+    constexpr int STAGE_BYTES = LAYOUT == PARO_VT ? ELEMS * (BITS == 16 ? 2 : 1) : 16;
+    __shared__ __attribute__((aligned(16))) uint8_t stage[STAGE_BYTES];
+    __shared__ float wave_amax[4];
+
+    const int blk = blockIdx.x;
+    const int bh = blockIdx.y;
+    const int tid = threadIdx.x;
+    const size_t group = (size_t)bh * kblocks + blk;
+    const InT* tile = xp + group * ELEMS;
+    uint8_t* out = codes + group * OUT_BYTES;
+
+    float x[IT][8];
+    float amax = 0.0f;
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+        const int chunk = tid + 256 * it;
+        const int row = (chunk * 8) / D;
+        const bool live = chunk < CHUNKS && blk * BLK + row < n_tokens;
+        if (live) {
+            load8<InT>(tile + (size_t)chunk * 8, x[it]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[it][e] = 0.0f;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(x[it][e]));
+    }
+
+    float scale = 1.0f;
+    if constexpr (BITS != 16) {
+        amax = wave_max(amax);
+        if ((tid & 63) == 0) wave_amax[tid >> 6] = amax;
+        __syncthreads();
+        amax = fmaxf(fmaxf(wave_amax[0], wave_amax[1]), fmaxf(wave_amax[2], wave_amax[3]));
+        if (amax > 0.0f) scale = amax / QMAX;  // correctly rounded binary32 divide
+    }
+    if (tid == 0) scales[group] = scale;
+
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+        const int chunk = tid + 256 * it;
+        if (chunk >= CHUNKS) continue;
+        const int row = (chunk * 8) / D;
+        const int c0 = (chunk * 8) % D;
+        if constexpr (BITS == 16) {
+            unsigned h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h[e] = f32_to_bf16_bits(x[it][e]);
+            if constexpr (LAYOUT == PARO_ROWS) {
+                uint4 w = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+                *(uint4*)(out + (size_t)chunk * 16) = w;
+            } else {
+                uint16_t* st = (uint16_t*)stage;
+                const int slot = vt_slot(row);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) st[(c0 + e) * BLK + slot] = (uint16_t)h[e];
+            }
+        } else {
+            int q[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float r = rintf(x[it][e] / scale);  // v_rndne_f32: round half to even
+                q[e] = (int)fminf(fmaxf(r, -QMAX), QMAX);
+            }
+            if constexpr (LAYOUT == PARO_ROWS) {
+                if constexpr (BITS == 8) {
+                    uint2 w;
+                    w.x = (q[0] & 0xff) | ((q[1] & 0xff) << 8) | ((q[2] & 0xff) << 16) | ((unsigned)q[3] << 24);
+                    w.y = (q[4] & 0xff) | ((q[5] & 0xff) << 8) | ((q[6] & 0xff) << 16) | ((unsigned)q[7] << 24);
+                    *(uint2*)(out + (size_t)chunk * 8) = w;
+                } else {
+                    unsigned w = 0;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) w |= (unsigned)(q[e] & 0xf) << (4 * e);
+                    *(unsigned*)(out + (size_t)chunk * 4) = w;
+                }
+            } else {
+                const int slot = vt_slot(row);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) stage[(c0 + e) * BLK + slot] = (uint8_t)q[e];
+            }
+        }
+    }
+
+    if constexpr (LAYOUT == PARO_VT) {
+        __syncthreads();
+        if constexpr (BITS == 4) {
+            // 8 consecutive slots of one channel -> 4 bytes: byte t = slot t | slot 4+t << 4
+            constexpr int GROUPS = ELEMS / 8;
+            for (int g = tid; g < GROUPS; g += 256) {
+                const uint2 s = *(const uint2*)(stage + g * 8);
+                *(unsigned*)(out + (size_t)g * 4) = (s.x & 0x0f0f0f0fu) | ((s.y & 0x0f0f0f0fu) << 4);
+            }
+        } else {
+            constexpr int VEC = STAGE_BYTES / 16;
+            for (int v = tid; v < VEC; v += 256) ((uint4*)out)[v] = ((const uint4*)stage)[v];
+        }
+    }
+}
+
+template <typename InT, int BLK, int D, int BITS>
+static void launch_layout(paro_layout layout, dim3 grid, hipStream_t st, const void* xp, void* codes, float* scales, int n, int k) {
+    if (layout == PARO_ROWS)
+        hipLaunchKernelGGL((quantize_kernel<InT, BLK, D, BITS, PARO_ROWS>), grid, dim3(256), 0, st, (const InT*)xp, (uint8_t*)codes, scales, n, k);
+    else
+        hipLaunchKernelGGL((quantize_kernel<InT, BLK, D, BITS, PARO_VT>), grid, dim3(256), 0, st, (const InT*)xp, (uint8_t*)codes, scales, n, k);
+}
+
+template <typename InT, int BLK, int D>
+static void launch_bits(int bits, paro_layout layout, dim3 grid, hipStream_t st, const void* xp, void* codes, float* scales, int n, int k) {
+    if (bits == 8) launch_layout<InT, BLK, D, 8>(layout, grid, st, xp, codes, scales, n, k);
+    else if (bits == 4) launch_layout<InT, BLK, D, 4>(layout, grid, st, xp, codes, scales, n, k);
+    else launch_layout<InT, BLK, D, 16>(layout, grid, st, xp, codes, scales, n, k);
+}
+
+template <typename InT>
+static void launch_shape(int blk, int d, int bits, paro_layout layout, dim3 grid, hipStream_t st, const void* xp, void* codes,
+                         float* scales, int n, int k) {
+    if (blk == 64 && d == 64) launch_bits<InT, 64, 64>(bits, layout, grid, st, xp, codes, scales, n, k);
+    else if (blk == 64 && d == 128) launch_bits<InT, 64, 128>(bits, layout, grid, st, xp, codes, scales, n, k);
+    else if (blk == 32 && d == 64) launch_bits<InT, 32, 64>(bits, layout, grid, st, xp, codes, scales, n, k);
+    else launch_bits<InT, 32, 128>(bits, layout, grid, st, xp, codes, scales, n, k);
+}
+
+}  // namespace paro
+
+extern "C" int paro_quantize(const paro_shape* s, paro_dtype dtype, int bits, paro_layout layout, const void* xp,
+                             void* codes, float* scales, void* stream) {
+    using namespace paro;
+    int64_t n, k;
+    if (int st = check_shape(s, &n, &k)) return st;
+    if (dtype != PARO_F32 && dtype != PARO_BF16) return fail(PARO_EINVAL, "dtype=%d is not a paro_dtype", (int)dtype);
+    if (bits != 8 && bits != 4 && bits != 16) return fail(PARO_EINVAL, "bits=%d: expected 8, 4 or 16", bits);
+    if (layout != PARO_ROWS && layout != PARO_VT) return fail(PARO_EINVAL, "layout=%d is not a paro_layout", (int)layout);
+    if (!xp || !codes || !scales) return fail(PARO_EINVAL, "xp, codes and scales must not be NULL");
+    if (((uintptr_t)xp | (uintptr_t)codes) & 15) return fail(PARO_EINVAL, "xp and codes must be 16-byte aligned");
+    if (xp == codes) return fail(PARO_EINVAL, "xp and codes must not alias");
+    if (k > 65535 * 32768LL) return fail(PARO_EUNSUPPORTED, "too many blocks");
+    dim3 grid((unsigned)k, (unsigned)(s->B * s->nh));
+    if (dtype == PARO_F32)
+        launch_shape<float>(s->block, s->d, bits, layout, grid, (hipStream_t)stream, xp, codes, scales, (int)n, (int)k);
+    else
+        launch_shape<uint16_t>(s->block, s->d, bits, layout, grid, (hipStream_t)stream, xp, codes, scales, (int)n, (int)k);
+    return check_launch("paro_quantize");
+}

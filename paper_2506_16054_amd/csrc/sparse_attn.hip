@@ -1,0 +1,348 @@
+// Block-sparse attention over the live blocks of a static per-head mask with INT8 QK^T and
+// INT8 / INT4 PV under block-wise scales (paper Sec. 4.2 (2) and Sec. 4.3), for gfx950.
+//
+// Work split.  One workgroup owns one row block (BLK queries) of one head and walks that row's
+// compacted live-block list in ascending order.  A wavefront owns 32 queries; BLK = 64 uses two
+// wavefronts, BLK = 32 one.  Both products run on v_mfma_i32_32x32x32_i8 in the transposed
+// orientation
+//        S^T (keys x queries)   = K_j (A operand, from LDS)   x Q_i^T (B operand, registers)
+//        O^T (channels x queries) = V_j^T (A operand, from LDS) x P^T   (B operand, registers)
+// because the accumulator layout of a 32x32 result tile gives every lane 16 values of ONE
+// query (keys 8q + 4g + p of the tile, q,p = 0..3, g = lane / 32): row reductions of the
+// softmax are in-lane plus one cross-lane step, and the 16 quantized probabilities pack into
+// exactly the four registers the next matrix instruction wants as its B operand.  The key
+// order this imposes on the contraction is matched by the PARO_VT storage order of V, so V
+// fragments are plain 16-byte LDS reads.
+//
+// Pipeline.  K_j and V_j^T tiles travel HBM/L2 -> registers -> LDS through a ring of three LDS
+// stages, two blocks ahead of the math, with ONE workgroup barrier per live block; the barrier
+// also carries the cross-wavefront exchange of the P-tile maximum (the P quantization group is
+// the whole BLK x BLK tile).
+//
+// Arithmetic per live block (X in log2 units, c = sq_i * sk_j * log2(e) / sqrt(d)):
+//   the i32 accumulator of S^T starts at the bit pattern of 1.5 * 2^23, so the same register
+//   read as a float is 1.5*2^23 + S exactly (|S| <= 127*127*128 < 2^22): no int->float convert;
+//   m' = max(m, c * rowmax S);  e = max over valid rows of (c * rowmax S - m')   (<= 0)
+//   E  = qmaxP * 2^(c*S - m' - e)  in (0, qmaxP]  ->  Pc = round(E) (magic-number rounding),
+//   l  = l * 2^(m - m') + sP * rowsum(E),  sP = 2^e / qmaxP   (the P tile maximum over qmaxP)
+//   acc = acc * 2^(m - m') + (sP * sv_j) * float(Pc V_j)
+#include "common.h"
+
+namespace paro {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+struct AttnArgs {
+    const uint8_t* q;
+    const uint8_t* k;
+    const uint8_t* v;
+    const float* sq;
+    const float* sk;
+    const float* sv;
+    const int* row_ptr;
+    const int* col_idx;
+    void* op;
+    int nnz;
+    int nh;
+    int kblocks;
+    int n_tokens;
+    int total_wg;  // B * nh * kblocks
+    int per_xcd;   // ceil(total_wg / 8)
+    float qk_scale;  // log2(e) / sqrt(d)
+};
+
+constexpr int kMagicI = 0x4B400000;       // bit pattern of 12582912.0f = 1.5 * 2^23
+constexpr float kMagicF = 12582912.0f;
+
+__device__ inline unsigned bf16_rne(float f) {
+    const unsigned u = __float_as_uint(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+__device__ inline void store4(float* p, float a, float b, float c, float d) { *(float4*)p = make_float4(a, b, c, d); }
+__device__ inline void store4(uint16_t* p, float a, float b, float c, float d) {
+    *(uint2*)p = make_uint2(bf16_rne(a) | (bf16_rne(b) << 16), bf16_rne(c) | (bf16_rne(d) << 16));
+}
+
+template <int BLK, int D, int PVBITS, typename OutT>
+__global__ __launch_bounds__(BLK * 2) void attn_i8_kernel(AttnArgs a) {
+    constexpr int NW = BLK / 32;
+    constexpr int NT = 64 * NW;
+    constexpr int KSTR = D + 16;    // padded LDS row strides: rows 16 B apart in bank space
+    constexpr int VSTR = BLK + 16;
+    constexpr int KBYTES = BLK * KSTR;
+    constexpr int VBYTES = D * VSTR;
+    constexpr int STAGE = KBYTES + VBYTES;
+    constexpr int VPACK = PVBITS == 4 ? 2 : 1;
+    constexpr int NKC = BLK * D / 16 / NT;          // 16-byte pieces of a K tile per thread
+    constexpr int NVC = BLK * D / VPACK / 16 / NT;  // 16-byte pieces of a V tile per thread
+    constexpr int KS = D / 32;    // contraction steps of QK^T
+    constexpr int KT = BLK / 32;  // 32-key tiles per block
+    constexpr int DT = D / 32;    // 32-channel tiles of the output
+    constexpr float QMAXP = PVBITS == 4 ? 7.0f : 127.0f;
+    constexpr float LOG2_QMAXP = PVBITS == 4 ? 2.807354922057604f : 6.988684686772166f;
+    static_assert(NKC >= 1 && NVC >= 1, "tile too small for the workgroup");
+
+    __shared__ __attribute__((aligned(16))) uint8_t lds[3 * STAGE];
+    __shared__ float tile_e[2][NW];
+
+    // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of
+    // (head, row block) so the K/V of the heads it works on stay in its own L2.
+    const int wg = blockIdx.x;
+    const int logical = (wg & 7) * a.per_xcd + (wg >> 3);
+    if (logical >= a.total_wg) return;
+    const int bh = logical / a.kblocks;
+    const int i = logical - bh * a.kblocks;
+    const int h = bh % a.nh;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = tid >> 6;
+    const int n = lane & 31;
+    const int g = lane >> 5;
+
+    const int* rp = a.row_ptr + (size_t)h * (a.kblocks + 1) + i;
+    const int beg = min(max(rp[0], 0), a.nnz);
+    const int end = min(max(rp[1], beg), a.nnz);
+    const int cnt = end - beg;
+    const int* cols = a.col_idx + beg;
+
+    const size_t head_rows = (size_t)bh * a.kblocks * BLK;
+    const int row = i * BLK + 32 * w + n;  // this lane's query, in the reordered sequence
+    const bool row_valid = row < a.n_tokens;
+    const uint8_t* kbase = a.k + head_rows * D;
+    const uint8_t* vbase = a.v + head_rows * D / VPACK;
+    const float* skp = a.sk + (size_t)bh * a.kblocks;
+    const float* svp = a.sv + (size_t)bh * a.kblocks;
+    const float sq_i = a.sq[(size_t)bh * a.kblocks + i] * a.qk_scale;
+
+    v4i qf[KS];
+    {
+        const uint8_t* qrow = a.q + (head_rows + row) * D + 16 * g;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qf[s] = *(const v4i*)(qrow + 32 * s);
+    }
+
+    v4i kreg[NKC], vreg[NVC];
+    auto col_of = [&](int t) { return min(max(cols[t], 0), a.kblocks - 1); };
+    auto gload = [&](int t) {
+        const int j = col_of(t);
+        const uint8_t* kp = kbase + (size_t)j * (BLK * D);
+        const uint8_t* vp = vbase + (size_t)j * (BLK * D / VPACK);
+#pragma unroll
+        for (int c = 0; c < NKC; ++c) kreg[c] = *(const v4i*)(kp + 16 * (tid + NT * c));
+#pragma unroll
+        for (int c = 0; c < NVC; ++c) vreg[c] = *(const v4i*)(vp + 16 * (tid + NT * c));
+    };
+    auto lstore = [&](int stage) {
+        uint8_t* ks = lds + stage * STAGE;
+        uint8_t* vs = ks + KBYTES;
+#pragma unroll
+        for (int c = 0; c < NKC; ++c) {
+            const int o = 16 * (tid + NT * c);
+            *(v4i*)(ks + (o / D) * KSTR + (o % D)) = kreg[c];
+        }
+#pragma unroll
+        for (int c = 0; c < NVC; ++c) {
+            const int o = 16 * (tid + NT * c);
+            if constexpr (PVBITS == 4) {
+                // 16 packed bytes = 32 slots of one channel.  A nibble moved to the top of its
+                // byte is the code times 16 as a signed byte; the factor is undone in the scale.
+                constexpr int PROW = BLK / 2;
+                const v4i x = vreg[c];
+                const v4i lo = (x << 4) & (int)0xF0F0F0F0;
+                const v4i hi = x & (int)0xF0F0F0F0;
+                uint8_t* dst = vs + (o / PROW) * VSTR + 2 * (o % PROW);
+                *(v4i*)dst = v4i{lo.x, hi.x, lo.y, hi.y};
+                *(v4i*)(dst + 16) = v4i{lo.z, hi.z, lo.w, hi.w};
+            } else {
+                *(v4i*)(vs + (o / BLK) * VSTR + (o % BLK)) = vreg[c];
+            }
+        }
+    };
+
+    float m = -INFINITY;  // running row maximum, log2 units
+    float l = 0.0f;       // this lane's share of the running denominator
+    float acc[DT][16];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[dt][r] = 0.0f;
+
+    if (cnt > 0) {
+        gload(0);
+        lstore(0);
+    }
+    if (cnt > 1) gload(1);
+    __syncthreads();
+
+    const bool ragged = (a.n_tokens % BLK) != 0;
+    int stage = 0;
+    for (int t = 0; t < cnt; ++t) {
+        const int next = stage == 2 ? 0 : stage + 1;
+        if (t + 1 < cnt) lstore(next);
+        if (t + 2 < cnt) gload(t + 2);
+
+        const int j = col_of(t);
+        const float c = sq_i * skp[j];
+        const uint8_t* ks = lds + stage * STAGE;
+        const uint8_t* vs = ks + KBYTES;
+
+        // ---- S^T = K_j Q_i^T, accumulators pre-loaded with the magic constant
+        v16i sacc[KT];
+#pragma unroll
+        for (int T = 0; T < KT; ++T) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[T][r] = kMagicI;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const v4i kf = *(const v4i*)(ks + (32 * T + n) * KSTR + 32 * s + 16 * g);
+                sacc[T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf[s], sacc[T], 0, 0, 0);
+            }
+        }
+        if (ragged && j == a.kblocks - 1) {  // keys past N never receive probability mass
+            const int nkeys = a.n_tokens - j * BLK;
+#pragma unroll
+            for (int T = 0; T < KT; ++T)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (32 * T + 8 * (r >> 2) + 4 * g + (r & 3) >= nkeys) sacc[T][r] = __float_as_int(-INFINITY);
+        }
+
+        // ---- running maximum and the tile's quantization scale
+        float mx = -INFINITY;
+#pragma unroll
+        for (int T = 0; T < KT; ++T)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, __int_as_float(sacc[T][r]));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float ymax = c * (mx - kMagicF);
+        const float m_new = fmaxf(m, ymax);
+        float e = row_valid ? ymax - m_new : -INFINITY;
+#pragma unroll
+        for (int off = 16; off >= 1; off >>= 1) e = fmaxf(e, __shfl_xor(e, off));
+        if constexpr (NW > 1) {
+            if (lane == 0) tile_e[t & 1][w] = e;
+        }
+        __syncthreads();
+        if constexpr (NW > 1) {
+#pragma unroll
+            for (int ww = 0; ww < NW; ++ww) e = fmaxf(e, tile_e[t & 1][ww]);
+        }
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        const float s_p = __builtin_amdgcn_exp2f(e) * (1.0f / QMAXP);
+        const float k0 = fmaf(-c, kMagicF, LOG2_QMAXP - m_new - e);
+        m = m_new;
+
+        // ---- E = qmaxP * 2^(X - m' - e); row sum; round to integer codes; pack as B operand
+        float rs = 0.0f;
+        v4i pf[KT];
+#pragma unroll
+        for (int T = 0; T < KT; ++T) {
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                unsigned b[4];
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const float ev = __builtin_amdgcn_exp2f(fmaf(__int_as_float(sacc[T][4 * qd + p]), c, k0));
+                    rs += ev;
+                    b[p] = __float_as_uint(ev + kMagicF);  // low byte = round-half-even(ev)
+                }
+                const unsigned lo = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
+                const unsigned hi = __builtin_amdgcn_perm(b[3], b[2], 0x04000c0cu);
+                pf[T][qd] = (int)(lo | hi);
+            }
+        }
+        l = fmaf(l, alpha, rs * s_p);
+
+        // ---- O^T += V_j^T P^T
+        const float sv_eff = s_p * svp[j] * (PVBITS == 4 ? 0.0625f : 1.0f);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            v16i o;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[r] = 0;
+#pragma unroll
+            for (int T = 0; T < KT; ++T) {
+                const v4i vf = *(const v4i*)(vs + (32 * dt + n) * VSTR + 32 * T + 16 * g);
+                o = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf[T], o, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[dt][r] = fmaf(acc[dt][r], alpha, sv_eff * (float)o[r]);
+        }
+        stage = next;
+    }
+
+    // ---- finalize: divide by the denominator, store the row (zeros for padded rows)
+    const float l_tot = l + __shfl_xor(l, 32);
+    const float inv = (row_valid && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
+    OutT* orow = (OutT*)a.op + (head_rows + row) * D + 4 * g;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd)
+            store4(orow + 32 * dt + 8 * qd, acc[dt][4 * qd] * inv, acc[dt][4 * qd + 1] * inv, acc[dt][4 * qd + 2] * inv,
+                   acc[dt][4 * qd + 3] * inv);
+}
+
+template <int BLK, int D, int PVBITS>
+static void launch_out(paro_dtype out_dtype, const AttnArgs& a, hipStream_t st) {
+    dim3 grid((unsigned)(a.per_xcd * 8));
+    if (out_dtype == PARO_F32)
+        hipLaunchKernelGGL((attn_i8_kernel<BLK, D, PVBITS, float>), grid, dim3(BLK * 2), 0, st, a);
+    else
+        hipLaunchKernelGGL((attn_i8_kernel<BLK, D, PVBITS, uint16_t>), grid, dim3(BLK * 2), 0, st, a);
+}
+
+template <int PVBITS>
+static void launch_i8(int blk, int d, paro_dtype out_dtype, const AttnArgs& a, hipStream_t st) {
+    if (blk == 64 && d == 64) launch_out<64, 64, PVBITS>(out_dtype, a, st);
+    else if (blk == 64 && d == 128) launch_out<64, 128, PVBITS>(out_dtype, a, st);
+    else if (blk == 32 && d == 64) launch_out<32, 64, PVBITS>(out_dtype, a, st);
+    else launch_out<32, 128, PVBITS>(out_dtype, a, st);
+}
+
+}  // namespace paro
+
+extern "C" int paro_sparse_attn(const paro_shape* s, int bits_qk, int bits_pv, const void* q, const float* sq, const void* k,
+                                const float* sk, const void* v, const float* sv, const int32_t* row_ptr,
+                                const int32_t* col_idx, int64_t nnz, paro_dtype out_dtype, void* op, void* stream) {
+    using namespace paro;
+    int64_t n, kb;
+    if (int st = check_shape(s, &n, &kb)) return st;
+    const bool i8 = bits_qk == 8 && (bits_pv == 8 || bits_pv == 4);
+    const bool b16 = bits_qk == 16 && bits_pv == 16;
+    if (!i8 && !b16) {
+        const bool known = (bits_qk == 8 || bits_qk == 16) && (bits_pv == 8 || bits_pv == 4 || bits_pv == 16);
+        return fail(known ? PARO_EUNSUPPORTED : PARO_EINVAL, "bits (qk=%d, pv=%d): supported pairs are (8,8), (8,4), (16,16)", bits_qk, bits_pv);
+    }
+    if (out_dtype != PARO_F32 && out_dtype != PARO_BF16) return fail(PARO_EINVAL, "out_dtype=%d is not a paro_dtype", (int)out_dtype);
+    if (!q || !k || !v || !op || !row_ptr) return fail(PARO_EINVAL, "q, k, v, op and row_ptr must not be NULL");
+    if (i8 && (!sq || !sk || !sv)) return fail(PARO_EINVAL, "sq, sk and sv are required for integer operands");
+    if (nnz < 0 || nnz > 0x7fffffffLL) return fail(PARO_EINVAL, "nnz=%lld out of range", (long long)nnz);
+    if (nnz > 0 && !col_idx) return fail(PARO_EINVAL, "col_idx is NULL but nnz=%lld", (long long)nnz);
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)op) & 15) return fail(PARO_EINVAL, "q, k, v and op must be 16-byte aligned");
+    if (b16) return fail(PARO_EUNSUPPORTED, "the bf16 mode is not built yet");
+
+    AttnArgs a;
+    a.q = (const uint8_t*)q;
+    a.k = (const uint8_t*)k;
+    a.v = (const uint8_t*)v;
+    a.sq = sq;
+    a.sk = sk;
+    a.sv = sv;
+    a.row_ptr = row_ptr;
+    a.col_idx = col_idx;
+    a.op = op;
+    a.nnz = (int)nnz;
+    a.nh = s->nh;
+    a.kblocks = (int)kb;
+    a.n_tokens = (int)n;
+    a.total_wg = (int)((int64_t)s->B * s->nh * kb);
+    a.per_xcd = (a.total_wg + 7) / 8;
+    a.qk_scale = (float)(1.4426950408889634 / sqrt((double)s->d));
+    if (bits_pv == 8) launch_i8<8>(s->block, s->d, out_dtype, a, (hipStream_t)stream);
+    else launch_i8<4>(s->block, s->d, out_dtype, a, (hipStream_t)stream);
+    return check_launch("paro_sparse_attn");
+}

@@ -1,0 +1,245 @@
+"""GPU parity: every step of the HIP path, called through the C ABI, against the CPU oracle on
+identical seeded inputs.  Integer work (gather rows, codes, scales, block lists) must match bit
+for bit; attention outputs within max-abs 2e-2 and relative-L2 1e-2 (the stated bar)."""
+import numpy as np
+import pytest
+
+from oracle import paro_oracle as po
+from paper_2506_16054_amd import workloads as wl
+from tests.helpers import blocklist_for, gather_fn, oracle_head, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS = 2e-2
+REL_L2 = 1e-2
+
+
+def _torch():
+    import torch
+
+    return torch
+
+
+def _pb():
+    from paper_2506_16054_amd import binding as pb
+
+    return pb
+
+
+def to_dev(x, dtype):
+    torch = _torch()
+    t = torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def tdtype(name):
+    torch = _torch()
+    return torch.bfloat16 if name == "bf16" else torch.float32
+
+
+def host(t):
+    return t.float().cpu().numpy() if t.dtype == _torch().bfloat16 else t.cpu().numpy()
+
+
+def vt_to_rows(vt, block):
+    """[k, d, block] in slot order -> [k*block, d] in token order (the documented PARO_VT map)."""
+    pb = _pb()
+    slots = np.array([pb.paro_vt_slot(block, i) for i in range(block)])
+    k, d, _ = vt.shape
+    return vt[:, :, slots].transpose(0, 2, 1).reshape(k * block, d)
+
+
+def unpack_vt_int4(b):
+    """bytes [k, d, block/2] -> int codes [k, d, block] in slot order: byte 4g+t holds slot 8g+t in
+    bits 0-3 and slot 8g+4+t in bits 4-7."""
+    u = b.astype(np.uint8)
+    k, d, half = u.shape
+    out = np.zeros((k, d, half * 2), np.int32)
+    for t4 in range(half):
+        g, t = divmod(t4, 4)
+        out[:, :, 8 * g + t] = ((u[:, :, t4] & 0xF).astype(np.int32) ^ 8) - 8
+        out[:, :, 8 * g + 4 + t] = ((u[:, :, t4] >> 4).astype(np.int32) ^ 8) - 8
+    return out
+
+
+def unpack_rows_int4(b):
+    u = b.astype(np.uint8)
+    out = np.zeros(u.shape[:-1] + (u.shape[-1] * 2,), np.int32)
+    out[..., 0::2] = ((u & 0xF).astype(np.int32) ^ 8) - 8
+    out[..., 1::2] = ((u >> 4).astype(np.int32) ^ 8) - 8
+    return out
+
+
+SMALL = {
+    # several 64-blocks, ragged tail (780 = 12*64 + 12), three heads with different orders
+    "video64": wl.Workload("video64", 1, 3, 64, 5, 12, 13, 0, 64, 0.4, 8, 8, "bf16", 11, perm_choice=(3, 0, 5)),
+    "video64_int4": wl.Workload("video64_int4", 1, 2, 64, 5, 12, 13, 0, 64, 0.4, 8, 4, "bf16", 12, perm_choice=(1, 4)),
+    "video32_f32": wl.Workload("video32_f32", 2, 2, 64, 3, 7, 9, 0, 32, 0.5, 8, 8, "f32", 13, perm_choice=(2, 5)),
+    "flux128": wl.Workload("flux128", 1, 2, 128, 1, 16, 16, 64, 64, 0.3, 8, 8, "bf16", 14, perm_choice=(0, 5)),
+    "flux128_b32_int4": wl.Workload("flux128_b32_int4", 1, 2, 128, 1, 8, 12, 32, 32, 0.5, 8, 4, "f32", 15, perm_choice=(5, 0)),
+    "tiny": wl.WORKLOADS["tiny"],
+}
+
+
+class Problem:
+    """Inputs, oracle results and GPU results of one small workload."""
+
+    def __init__(self, w):
+        torch, pb = _torch(), _pb()
+        from paper_2506_16054_amd.pipeline import ParoAttention
+
+        self.w = w
+        self.perm_ids = wl.make_perm_ids(w)
+        self.masks = wl.make_block_masks(w, gather_fn(w), self.perm_ids)
+        self.bits, self.row_ptr, self.col_idx = blocklist_for(w, self.masks)
+        self.q, self.k, self.v = wl.make_qkv(w)
+        self.oracle = [[oracle_head(w, self.q[b, h], self.k[b, h], self.v[b, h], self.perm_ids[h], self.row_ptr[h], self.col_idx)
+                        for h in range(w.nh)] for b in range(w.B)]
+        self.s = pb.shape_of(w)
+        self.pa = ParoAttention(self.s, self.perm_ids, self.bits, w.bits_qk, w.bits_pv, tdtype(w.dtype))
+        self.dq, self.dk, self.dv = (to_dev(x, w.dtype) for x in (self.q, self.k, self.v))
+        # poison the outputs so that untouched elements are noticed
+        for t in self.pa.xp + [self.pa.op, self.pa.o]:
+            t.fill_(float("nan"))
+        self.o = self.pa.run(self.dq, self.dk, self.dv)
+        torch.cuda.synchronize()
+
+
+_cache = {}
+
+
+def problem(name):
+    if name not in _cache:
+        _cache[name] = Problem(SMALL[name])
+    return _cache[name]
+
+
+ALL = list(SMALL)
+
+
+@pytest.mark.parametrize("name", ALL)
+def test_blocklist_bit_exact(name):
+    p = problem(name)
+    assert np.array_equal(p.pa.h_row_ptr, p.row_ptr)
+    assert np.array_equal(p.pa.h_col_idx, p.col_idx)
+
+
+@pytest.mark.parametrize("name", ALL)
+def test_permute_bit_exact(name):
+    p = problem(name)
+    w = p.w
+    for x, xp in zip((p.q, p.k, p.v), p.pa.xp):
+        got = host(xp)
+        assert not np.isnan(got).any()
+        for b in range(w.B):
+            for h in range(w.nh):
+                idx = p.oracle[b][h]["idx"]
+                assert np.array_equal(got[b, h], po.permute(x[b, h], idx, w.npad))
+
+
+@pytest.mark.parametrize("name", ALL)
+def test_quantize_codes_and_scales_bit_exact(name):
+    p = problem(name)
+    w = p.w
+    qc, kc = p.pa.qc.cpu().numpy(), p.pa.kc.cpu().numpy()
+    vc = p.pa.vc.cpu().numpy()
+    sq, sk, sv = (t.cpu().numpy() for t in (p.pa.sq, p.pa.sk, p.pa.sv))
+    for b in range(w.B):
+        for h in range(w.nh):
+            r = p.oracle[b][h]
+            assert np.array_equal(qc[b, h].astype(np.int32), r["qc"])
+            assert np.array_equal(kc[b, h].astype(np.int32), r["kc"])
+            v_slots = unpack_vt_int4(vc[b, h]) if w.bits_pv == 4 else vc[b, h].astype(np.int32)
+            assert np.array_equal(vt_to_rows(v_slots, w.block), r["vc"])
+            assert np.array_equal(sq[b, h], r["sq"]) and np.array_equal(sk[b, h], r["sk"]) and np.array_equal(sv[b, h], r["sv"])
+
+
+@pytest.mark.parametrize("name", ALL)
+def test_attention_matches_oracle(name):
+    p = problem(name)
+    w = p.w
+    op = host(p.pa.op)
+    o = host(p.o)
+    assert not np.isnan(op).any() and not np.isnan(o).any()
+    for b in range(w.B):
+        for h in range(w.nh):
+            r = p.oracle[b][h]
+            ref_p = po.cast_output(r["op"], w.dtype)
+            ref = po.cast_output(r["o"], w.dtype)
+            assert np.all(op[b, h, w.N:] == 0)  # padded rows are written as zeros
+            assert np.max(np.abs(op[b, h] - ref_p)) <= MAX_ABS, (name, b, h)
+            assert rel_l2(op[b, h], ref_p) <= REL_L2, (name, b, h)
+            assert np.max(np.abs(o[b, h] - ref)) <= MAX_ABS
+            assert rel_l2(o[b, h], ref) <= REL_L2
+
+
+@pytest.mark.parametrize("name", ["video64", "video32_f32"])
+def test_unpermute_bit_exact(name):
+    p = problem(name)
+    w = p.w
+    op, o = host(p.pa.op), host(p.o)
+    for b in range(w.B):
+        for h in range(w.nh):
+            assert np.array_equal(o[b, h], po.unpermute(op[b, h], p.oracle[b][h]["idx"]))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("bits,layout", [(8, "rows"), (8, "vt"), (4, "rows"), (4, "vt"), (16, "rows"), (16, "vt")])
+def test_quantize_all_modes_ragged(dtype, bits, layout):
+    """Every (dtype, bits, layout) of paro_quantize on a ragged shape, including garbage in the
+    padded rows (which must not influence scales or codes)."""
+    torch, pb = _torch(), _pb()
+    rng = np.random.default_rng(bits * 7 + len(layout))
+    B, nh, d, block = 1, 2, 64, 64
+    F, H, W = 2, 9, 11  # N = 198 = 3*64 + 6
+    s = pb.make_shape(B, nh, d, F, H, W, 0, block)
+    n, k, npad = 198, 4, 256
+    x = (rng.standard_normal((B, nh, npad, d)) * rng.uniform(0.2, 5, size=(B, nh, npad, 1))).astype(np.float32)
+    x[0, 1, 64:128] = 0  # an all-zero block
+    if dtype == "bf16":
+        x = wl.bf16_round(x)
+    x[:, :, n:] = 1000.0  # garbage where padding should be
+    xp = to_dev(x, dtype)
+    lay = pb.PARO_ROWS if layout == "rows" else pb.PARO_VT
+    codes = torch.full(pb.codes_shape(s, bits, lay), -1 if bits != 16 else float("nan"),
+                       dtype=torch.bfloat16 if bits == 16 else torch.int8, device="cuda:0")
+    scales = torch.full((B, nh, k), float("nan"), dtype=torch.float32, device="cuda:0")
+    pb.paro_quantize(s, bits, lay, xp, codes, scales)
+    torch.cuda.synchronize()
+    got_s = scales.cpu().numpy()
+    got = host(codes)
+    for h in range(nh):
+        if bits == 16:
+            ref = x[0, h].copy()
+            ref[n:] = 0
+            ref = wl.bf16_round(ref).astype(np.float32)
+            rows = got[0, h] if layout == "rows" else vt_to_rows(got[0, h], block)
+            assert np.array_equal(rows, ref)
+            assert np.all(got_s[0, h] == 1.0)
+            continue
+        ref_c, ref_s = po.quantize_blocks(x[0, h], n, block, po.qmax_of(bits))
+        if layout == "rows":
+            rows = unpack_rows_int4(got[0, h]) if bits == 4 else got[0, h].astype(np.int32)
+        else:
+            slots = unpack_vt_int4(got[0, h]) if bits == 4 else got[0, h].astype(np.int32)
+            rows = vt_to_rows(slots, block)
+        assert np.array_equal(rows, ref_c)
+        assert np.array_equal(got_s[0, h], ref_s)
+
+
+def test_empty_row_block_gives_zeros():
+    torch, pb = _torch(), _pb()
+    from paper_2506_16054_amd.pipeline import ParoAttention
+
+    w = SMALL["video64"].replace(nh=1, perm_choice=(3,))
+    masks = wl.make_block_masks(w, gather_fn(w))
+    masks[0, 2, :] = False  # row block 2 attends nothing
+    bits, row_ptr, col_idx = blocklist_for(w, masks)
+    q, k, v = wl.make_qkv(w)
+    pa = ParoAttention(pb.shape_of(w), wl.make_perm_ids(w), bits, 8, 8, torch.bfloat16)
+    pa.run(*(to_dev(x, "bf16") for x in (q, k, v)))
+    torch.cuda.synchronize()
+    op = host(pa.op)[0, 0]
+    r = oracle_head(w, q[0, 0], k[0, 0], v[0, 0], 3, row_ptr[0], col_idx)
+    assert np.all(op[128:192] == 0)
+    assert rel_l2(op, po.cast_output(r["op"], "bf16")) <= REL_L2

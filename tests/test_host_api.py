@@ -1,0 +1,118 @@
+"""The C-ABI library loads, exports every declared symbol, and its host-only entry points agree
+with the oracle bit for bit (CPU only: nothing here launches a kernel)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import paro_oracle as po
+from paper_2506_16054_amd import binding as pb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "paro.h")).read()
+    declared = set(re.findall(r"\b(paro_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(pb.EXPORTS)
+    L = pb.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert pb.paro_version() >= 1
+
+
+def test_shape_arithmetic_and_rejection():
+    s = pb.make_shape(1, 48, 64, 13, 30, 45, 0, 64)
+    assert (pb.paro_ntokens(s), pb.paro_nblocks(s), pb.paro_npad(s)) == (17550, 275, 17600)
+    s = pb.make_shape(1, 24, 128, 1, 64, 64, 512, 64)
+    assert (pb.paro_ntokens(s), pb.paro_nblocks(s)) == (4608, 72)
+    for bad in (pb.make_shape(1, 2, 48, 2, 2, 2, 0, 64), pb.make_shape(1, 2, 64, 2, 2, 2, 0, 16),
+                pb.make_shape(0, 2, 64, 2, 2, 2, 0, 64), pb.make_shape(1, 2, 64, 0, 2, 2, 0, 64),
+                pb.make_shape(1, 2, 64, 2, 2, 2, -1, 64), pb.make_shape(1, 300, 64, 2, 2, 2, 0, 64)):
+        with pytest.raises(pb.ParoError) as e:
+            pb.paro_ntokens(bad)
+        assert e.value.status in (pb.PARO_EINVAL, pb.PARO_EUNSUPPORTED)
+    assert pb.lib().paro_ntokens(None) == pb.PARO_EINVAL
+    assert pb.lib().paro_strerror(pb.PARO_EINVAL) == b"invalid argument"
+
+
+@pytest.mark.parametrize("grid,T", [((2, 8, 8), 0), ((3, 4, 5), 7), ((1, 6, 7), 0), ((13, 30, 45), 0), ((1, 64, 64), 512)])
+def test_perm_index_matches_oracle_bit_exactly(grid, T):
+    F, H, W = grid
+    s = pb.make_shape(1, 1, 64, F, H, W, T, 64)
+    for pid in range(6):
+        got = pb.paro_perm_index(s, pid)
+        assert got.dtype == np.int32
+        assert np.array_equal(got, po.perm_index(F, H, W, T, pid))
+    with pytest.raises(pb.ParoError):
+        pb.paro_perm_index(s, 6)
+    with pytest.raises(pb.ParoError):
+        pb.paro_perm_index(s, -1)
+
+
+@pytest.mark.parametrize("block", [32, 64])
+def test_vt_slot_is_the_documented_bijection(block):
+    slots = [pb.paro_vt_slot(block, i) for i in range(block)]
+    assert sorted(slots) == list(range(block))
+    for i in range(block):
+        # token i = 32*T + 8*q + 4*g + p  ->  slot 32*T + 16*g + 4*q + p
+        T, q, g, p = i // 32, (i % 32) // 8, (i % 8) // 4, i % 4
+        assert slots[i] == 32 * T + 16 * g + 4 * q + p
+    for bad in (-1, block):
+        with pytest.raises(pb.ParoError):
+            pb.paro_vt_slot(block, bad)
+    with pytest.raises(pb.ParoError):
+        pb.paro_vt_slot(48, 0)
+
+
+@pytest.mark.parametrize("nh,k", [(1, 1), (3, 4), (2, 11), (2, 275)])
+def test_blocklist_matches_oracle_bit_exactly(nh, k):
+    rng = np.random.default_rng(k)
+    m = rng.random((nh, k, k)) < 0.3
+    if nh > 1:
+        m[1, k // 2] = False  # an empty row
+    bits = np.packbits(m.reshape(nh, -1), axis=1, bitorder="little")
+    rp, ci = pb.paro_mask_to_blocklist(nh, k, bits)
+    rp_o, ci_o = po.mask_to_blocklist(bits, nh, k)
+    assert rp.dtype == np.int32 and ci.dtype == np.int32
+    assert np.array_equal(rp, rp_o) and np.array_equal(ci, ci_o)
+
+
+def test_blocklist_capacity_and_null_handling():
+    L = pb.lib()
+    bits = np.array([[0xFF, 0x01]], np.uint8)  # k = 3, all 9 blocks live
+    rp = np.zeros(4, np.int32)
+    ci = np.zeros(4, np.int32)
+    nnz = ctypes.c_int64(-1)
+    st = L.paro_mask_to_blocklist(1, 3, bits.ctypes.data, rp.ctypes.data, ci.ctypes.data, 4, ctypes.byref(nnz))
+    assert st == pb.PARO_EINVAL and nnz.value == 9
+    assert b"live blocks" in L.paro_last_error()
+    assert L.paro_mask_to_blocklist(1, 3, None, rp.ctypes.data, ci.ctypes.data, 4, ctypes.byref(nnz)) == pb.PARO_EINVAL
+    assert L.paro_mask_to_blocklist(1, 0, bits.ctypes.data, rp.ctypes.data, ci.ctypes.data, 4, ctypes.byref(nnz)) == pb.PARO_EINVAL
+    assert L.paro_mask_to_blocklist(1, 3, bits.ctypes.data, rp.ctypes.data, None, 4, ctypes.byref(nnz)) == pb.PARO_EINVAL
+
+
+def test_device_entry_points_reject_bad_arguments_before_launch():
+    # Host-side validation only: every call below must fail before any HIP call is made.
+    L = pb.lib()
+    s = pb.make_shape(1, 2, 64, 2, 8, 8, 0, 32)
+    perm = np.array([0, 9], np.uint8)
+    fake = ctypes.c_void_p(0x1000)
+    assert L.paro_permute(ctypes.byref(s), pb.PARO_F32, perm.ctypes.data, fake, ctypes.c_void_p(0x2000), None) == pb.PARO_EINVAL
+    assert b"perm_ids[1]" in L.paro_last_error()
+    ok = np.array([0, 5], np.uint8)
+    assert L.paro_permute(ctypes.byref(s), pb.PARO_F32, ok.ctypes.data, None, fake, None) == pb.PARO_EINVAL
+    assert L.paro_permute(ctypes.byref(s), pb.PARO_F32, ok.ctypes.data, fake, fake, None) == pb.PARO_EINVAL
+    assert L.paro_permute(ctypes.byref(s), 7, ok.ctypes.data, fake, ctypes.c_void_p(0x2000), None) == pb.PARO_EINVAL
+    assert L.paro_unpermute(ctypes.byref(s), pb.PARO_F32, ok.ctypes.data, fake, ctypes.c_void_p(0x2004), None) == pb.PARO_EINVAL
+    assert L.paro_quantize(ctypes.byref(s), pb.PARO_F32, 5, pb.PARO_ROWS, fake, ctypes.c_void_p(0x2000), fake, None) == pb.PARO_EINVAL
+    assert L.paro_quantize(ctypes.byref(s), pb.PARO_F32, 8, 3, fake, ctypes.c_void_p(0x2000), fake, None) == pb.PARO_EINVAL
+    assert L.paro_quantize(ctypes.byref(s), pb.PARO_F32, 8, pb.PARO_VT, fake, None, fake, None) == pb.PARO_EINVAL
+    args = [fake, fake, fake, fake, fake, fake, fake, fake]
+    assert L.paro_sparse_attn(ctypes.byref(s), 4, 8, *args, 4, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
+    assert L.paro_sparse_attn(ctypes.byref(s), 8, 16, *args, 4, pb.PARO_F32, fake, None) == pb.PARO_EUNSUPPORTED
+    assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, *args, -1, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
+    assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, fake, None, fake, fake, fake, fake, fake, fake, 4, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
+    assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, *args, 4, 5, fake, None) == pb.PARO_EINVAL
