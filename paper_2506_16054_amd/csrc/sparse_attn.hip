@@ -23,7 +23,8 @@
 //   the i32 accumulator of S^T starts at the bit pattern of 1.5 * 2^23, so the same register
 //   read as a float is 1.5*2^23 + S exactly (|S| <= 127*127*128 < 2^22): no int->float convert;
 //   m' = max(m, c * rowmax S);  e = max over valid rows of (c * rowmax S - m')   (<= 0)
-//   E  = qmaxP * 2^(c*S - m' - e)  in (0, qmaxP]  ->  Pc = round(E) (magic-number rounding),
+//   E  = qmaxP * 2^(c*S - m' - e)  in (0, qmaxP]  ->  Pc = round-half-even(E) by v_cvt_pk_u8_f32,
+//        which also packs four codes into one register,
 //   l  = l * 2^(m - m') + sP * rowsum(E),  sP = 2^e / qmaxP   (the P tile maximum over qmaxP)
 //   acc = acc * 2^(m - m') + (sP * sv_j) * float(Pc V_j)
 #include "common.h"
@@ -232,26 +233,33 @@ __global__ __launch_bounds__(BLK * 2) void attn_i8_kernel(AttnArgs a) {
         }
         const float alpha = __builtin_amdgcn_exp2f(m - m_new);
         const float s_p = __builtin_amdgcn_exp2f(e) * (1.0f / QMAXP);
-        const float k0 = fmaf(-c, kMagicF, LOG2_QMAXP - m_new - e);
+        // exponent offset: X - m' - e + log2(qmaxP), so that the tile maximum maps to qmaxP
+        const float off = LOG2_QMAXP - m_new - e;
+#ifdef PARO_FUSED_MAGIC
+        const float k0 = fmaf(-c, kMagicF, off);  // one fma per element, 2^-13 absolute in the exponent
+#endif
         m = m_new;
 
-        // ---- E = qmaxP * 2^(X - m' - e); row sum; round to integer codes; pack as B operand
+        // ---- E = qmaxP * 2^(X - m' - e); row sum; round half to even and pack as B operand
         float rs = 0.0f;
         v4i pf[KT];
 #pragma unroll
         for (int T = 0; T < KT; ++T) {
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
-                unsigned b[4];
+                unsigned pk = 0;
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
-                    const float ev = __builtin_amdgcn_exp2f(fmaf(__int_as_float(sacc[T][4 * qd + p]), c, k0));
+                    const float f = __int_as_float(sacc[T][4 * qd + p]);
+#ifdef PARO_FUSED_MAGIC
+                    const float ev = __builtin_amdgcn_exp2f(fmaf(f, c, k0));
+#else
+                    const float ev = __builtin_amdgcn_exp2f(fmaf(f - kMagicF, c, off));
+#endif
                     rs += ev;
-                    b[p] = __float_as_uint(ev + kMagicF);  // low byte = round-half-even(ev)
+                    pk = __builtin_amdgcn_cvt_pk_u8_f32(ev, p, pk);  // round-half-even, saturating
                 }
-                const unsigned lo = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
-                const unsigned hi = __builtin_amdgcn_perm(b[3], b[2], 0x04000c0cu);
-                pf[T][qd] = (int)(lo | hi);
+                pf[T][qd] = (int)pk;
             }
         }
         l = fmaf(l, alpha, rs * s_p);

@@ -6,7 +6,7 @@ import pytest
 
 from oracle import paro_oracle as po
 from paper_2506_16054_amd import workloads as wl
-from tests.helpers import blocklist_for, gather_fn, oracle_head, rel_l2
+from tests.helpers import blocklist_for, check_attention, gather_fn, oracle_head, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -167,10 +167,10 @@ def test_attention_matches_oracle(name):
             ref_p = po.cast_output(r["op"], w.dtype)
             ref = po.cast_output(r["o"], w.dtype)
             assert np.all(op[b, h, w.N:] == 0)  # padded rows are written as zeros
-            assert np.max(np.abs(op[b, h] - ref_p)) <= MAX_ABS, (name, b, h)
-            assert rel_l2(op[b, h], ref_p) <= REL_L2, (name, b, h)
-            assert np.max(np.abs(o[b, h] - ref)) <= MAX_ABS
-            assert rel_l2(o[b, h], ref) <= REL_L2
+            st = check_attention(op[b, h], ref_p, r["flip_risk"], MAX_ABS, REL_L2, "%s b%d h%d" % (name, b, h))
+            print("%s b%d h%d: max_abs %.2e rel_l2 %.2e rows with near-tie codes %.1f%%"
+                  % (name, b, h, st["max_abs"], st["rel_l2"], 100 * st["risky_rows"]))
+            check_attention(o[b, h], ref, po.unpermute(r["flip_risk"], r["idx"]), MAX_ABS, REL_L2)
 
 
 @pytest.mark.parametrize("name", ["video64", "video32_f32"])
@@ -242,4 +242,4 @@ def test_empty_row_block_gives_zeros():
     op = host(pa.op)[0, 0]
     r = oracle_head(w, q[0, 0], k[0, 0], v[0, 0], 3, row_ptr[0], col_idx)
     assert np.all(op[128:192] == 0)
-    assert rel_l2(op, po.cast_output(r["op"], "bf16")) <= REL_L2
+    check_attention(op, po.cast_output(r["op"], "bf16"), r["flip_risk"], MAX_ABS, REL_L2)

@@ -286,3 +286,27 @@ def test_cast_output_bf16_rounds_to_nearest_even():
     assert got[0] == 1.0 and got[1] == 1.0 and got[2] == 1.0 and got[3] == 1.0 + 2.0**-7
     assert abs(got[4] + 3.14159) < 2.0**-7
     assert po.cast_output(x, "f32")[4] == np.float32(-3.14159)
+
+
+def test_flip_risk_bounds_the_effect_of_a_rounding_tie():
+    # One 2x2 tile, d = 1, P = [[1, .5], [1, .5]] -> P / sP = [127, 63.5]: a tie.  Rounding the
+    # tie the other way moves the output by exactly sP * |v1| / l, which is what flip_risk reports.
+    n, block = 2, 2
+    q = np.ones((2, 1))
+    k = np.array([[0.0], [-math.log(2.0)]])
+    v = np.array([[3.0], [-5.0]])
+    ones = np.ones(1, np.float32)
+    rp, ci = np.array([0, 1], np.int32), np.array([0], np.int32)
+    diag = {}
+    o = po.sparse_attention_head(q, ones, k, ones, v, ones, n, block, rp, ci, 127, tie_tol=1e-9, diag=diag)
+    l = 1.5
+    up = (127 * 3.0 + 64 * -5.0) / 127 / l
+    down = (127 * 3.0 + 63 * -5.0) / 127 / l
+    assert np.allclose(o[:, 0], up, rtol=1e-12) or np.allclose(o[:, 0], down, rtol=1e-12)
+    assert np.allclose(diag["flip_risk"][:, 0], 5.0 / 127 / l, rtol=1e-12)
+    assert abs(up - down) <= diag["flip_risk"][0, 0] * (1 + 1e-12)
+    # away from ties nothing is flagged
+    diag2 = {}
+    k2 = np.array([[0.0], [-0.3]])
+    po.sparse_attention_head(q, ones, k2, ones, v, ones, n, block, rp, ci, 127, tie_tol=1e-9, diag=diag2)
+    assert np.all(diag2["flip_risk"] == 0)
