@@ -14,19 +14,20 @@
 // order this imposes on the contraction is matched by the PARO_VT storage order of V, so V
 // fragments are plain 16-byte LDS reads.
 //
-// Pipeline.  K_j and V_j^T tiles travel HBM/L2 -> registers -> LDS through a ring of three LDS
-// stages, two blocks ahead of the math, with ONE workgroup barrier per live block; the barrier
-// also carries the cross-wavefront exchange of the P-tile maximum (the P quantization group is
-// the whole BLK x BLK tile).
+// Pipeline.  K_j and V_j^T tiles travel HBM/L2 -> registers -> LDS through a ring of two LDS
+// stages, with the global loads issued two blocks ahead of the math and ONE workgroup barrier
+// per live block; the barrier also carries the cross-wavefront exchange of the P-tile maximum
+// (the P quantization group is the whole BLK x BLK tile).  Cross-lane reductions use DPP,
+// v_permlane32_swap and scalar reads, never LDS.
 //
 // Arithmetic per live block (X in log2 units, c = sq_i * sk_j * log2(e) / sqrt(d)):
-//   the i32 accumulator of S^T starts at the bit pattern of 1.5 * 2^23, so the same register
-//   read as a float is 1.5*2^23 + S exactly (|S| <= 127*127*128 < 2^22): no int->float convert;
-//   m' = max(m, c * rowmax S);  e = max over valid rows of (c * rowmax S - m')   (<= 0)
+//   m' = max(m, c * rowmax S)  (the row maximum is taken on the integers, c > 0);  e = max over valid rows of (c * rowmax S - m')   (<= 0)
 //   E  = qmaxP * 2^(c*S - m' - e)  in (0, qmaxP]  ->  Pc = round-half-even(E) by v_cvt_pk_u8_f32,
 //        which also packs four codes into one register,
 //   l  = l * 2^(m - m') + sP * rowsum(E),  sP = 2^e / qmaxP   (the P tile maximum over qmaxP)
 //   acc = acc * 2^(m - m') + (sP * sv_j) * float(Pc V_j)
+#include <type_traits>
+
 #include "common.h"
 
 namespace paro {
@@ -53,9 +54,6 @@ struct AttnArgs {
     float qk_scale;  // log2(e) / sqrt(d)
 };
 
-constexpr int kMagicI = 0x4B400000;       // bit pattern of 12582912.0f = 1.5 * 2^23
-constexpr float kMagicF = 12582912.0f;
-
 __device__ inline unsigned bf16_rne(float f) {
     const unsigned u = __float_as_uint(f);
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
@@ -66,8 +64,39 @@ __device__ inline void store4(uint16_t* p, float a, float b, float c, float d) {
     *(uint2*)p = make_uint2(bf16_rne(a) | (bf16_rne(b) << 16), bf16_rne(c) | (bf16_rne(d) << 16));
 }
 
+// ---- cross-lane helpers (no LDS traffic) ---------------------------------------------------
+template <int CTRL>
+__device__ inline int dpp_mov(int x) {
+    return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, true);
+}
+
+// max over lanes n and n + 32 (the two lanes that share a query), returned in both
+__device__ inline int xor32_max(int x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return max((int)r[0], (int)r[1]);
+}
+
+// Maximum over the wavefront of values that are all <= 0 (or -inf), as a wave-uniform value.
+// Rows of 16 lanes are reduced with DPP (xor 1, xor 2, half mirror, mirror); the row results
+// are read through scalar registers.  For non-positive floats a larger value has the smaller
+// bit pattern, so the scalar combine is an unsigned minimum.
+__device__ inline float wave_max_nonpositive(float x) {
+    x = fmaxf(x, __int_as_float(dpp_mov<0xB1>(__float_as_int(x))));   // quad_perm [1,0,3,2]
+    x = fmaxf(x, __int_as_float(dpp_mov<0x4E>(__float_as_int(x))));   // quad_perm [2,3,0,1]
+    x = fmaxf(x, __int_as_float(dpp_mov<0x141>(__float_as_int(x))));  // row_half_mirror
+    x = fmaxf(x, __int_as_float(dpp_mov<0x140>(__float_as_int(x))));  // row_mirror
+    const unsigned b = (unsigned)__float_as_int(x);
+    const unsigned r0 = __builtin_amdgcn_readlane(b, 0), r1 = __builtin_amdgcn_readlane(b, 16);
+    const unsigned r2 = __builtin_amdgcn_readlane(b, 32), r3 = __builtin_amdgcn_readlane(b, 48);
+    return __uint_as_float(min(min(r0, r1), min(r2, r3)));
+}
+
+#ifndef PARO_ATTN_WAVES_D64
+#define PARO_ATTN_WAVES_D64 4  // wavefronts per SIMD the register allocation must allow, d = 64
+#endif
+
 template <int BLK, int D, int PVBITS, typename OutT>
-__global__ __launch_bounds__(BLK * 2) void attn_i8_kernel(AttnArgs a) {
+__global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void attn_i8_kernel(AttnArgs a) {
     constexpr int NW = BLK / 32;
     constexpr int NT = 64 * NW;
     constexpr int KSTR = D + 16;    // padded LDS row strides: rows 16 B apart in bank space
@@ -85,7 +114,7 @@ __global__ __launch_bounds__(BLK * 2) void attn_i8_kernel(AttnArgs a) {
     constexpr float LOG2_QMAXP = PVBITS == 4 ? 2.807354922057604f : 6.988684686772166f;
     static_assert(NKC >= 1 && NVC >= 1, "tile too small for the workgroup");
 
-    __shared__ __attribute__((aligned(16))) uint8_t lds[3 * STAGE];
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * STAGE];
     __shared__ float tile_e[2][NW];
 
     // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of
@@ -136,14 +165,16 @@ __global__ __launch_bounds__(BLK * 2) void attn_i8_kernel(AttnArgs a) {
 #pragma unroll
         for (int c = 0; c < NVC; ++c) vreg[c] = *(const v4i*)(vp + 16 * (tid + NT * c));
     };
-    auto lstore = [&](int stage) {
+    auto lstore_k = [&](int stage) {
         uint8_t* ks = lds + stage * STAGE;
-        uint8_t* vs = ks + KBYTES;
 #pragma unroll
         for (int c = 0; c < NKC; ++c) {
             const int o = 16 * (tid + NT * c);
             *(v4i*)(ks + (o / D) * KSTR + (o % D)) = kreg[c];
         }
+    };
+    auto lstore_v = [&](int stage) {
+        uint8_t* vs = lds + stage * STAGE + KBYTES;
 #pragma unroll
         for (int c = 0; c < NVC; ++c) {
             const int o = 16 * (tid + NT * c);
@@ -171,62 +202,73 @@ __global__ __launch_bounds__(BLK * 2) void attn_i8_kernel(AttnArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[dt][r] = 0.0f;
 
+    // LDS ring of two stages, one barrier per live block (placed after the row maxima):
+    //   K_{t+1} is stored at the top of iteration t  - every wavefront finished reading K_{t-1}
+    //                                                  before barrier t-1;
+    //   V_{t+1} is stored right after barrier t      - every wavefront finished reading V_{t-1}
+    //                                                  before it arrived at barrier t;
+    //   the registers are refilled from global memory (block t+2) after both stores.
     if (cnt > 0) {
         gload(0);
-        lstore(0);
+        lstore_k(0);
+        lstore_v(0);
     }
     if (cnt > 1) gload(1);
     __syncthreads();
 
-    const bool ragged = (a.n_tokens % BLK) != 0;
     int stage = 0;
-    for (int t = 0; t < cnt; ++t) {
-        const int next = stage == 2 ? 0 : stage + 1;
-        if (t + 1 < cnt) lstore(next);
-        if (t + 2 < cnt) gload(t + 2);
+    // One live block.  TAIL selects the variant that masks keys past N (only the last column
+    // block of a ragged sequence needs it; keeping it out of the common path saves two
+    // instructions per logit).
+    auto step = [&](auto tail_tag, int t) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
+        const int next = stage ^ 1;
+        if (t + 1 < cnt) lstore_k(next);
 
         const int j = col_of(t);
         const float c = sq_i * skp[j];
         const uint8_t* ks = lds + stage * STAGE;
         const uint8_t* vs = ks + KBYTES;
 
-        // ---- S^T = K_j Q_i^T, accumulators pre-loaded with the magic constant
+        // ---- S^T = K_j Q_i^T (i32)
         v16i sacc[KT];
 #pragma unroll
         for (int T = 0; T < KT; ++T) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[T][r] = kMagicI;
+            for (int r = 0; r < 16; ++r) sacc[T][r] = 0;
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 const v4i kf = *(const v4i*)(ks + (32 * T + n) * KSTR + 32 * s + 16 * g);
                 sacc[T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf[s], sacc[T], 0, 0, 0);
             }
         }
-        if (ragged && j == a.kblocks - 1) {  // keys past N never receive probability mass
+        constexpr int kMaskedS = -(1 << 30);  // below any reachable sum; its exponential is 0
+        if constexpr (TAIL) {  // keys past N never receive probability mass
             const int nkeys = a.n_tokens - j * BLK;
 #pragma unroll
             for (int T = 0; T < KT; ++T)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    if (32 * T + 8 * (r >> 2) + 4 * g + (r & 3) >= nkeys) sacc[T][r] = __float_as_int(-INFINITY);
+                    if (32 * T + 8 * (r >> 2) + 4 * g + (r & 3) >= nkeys) sacc[T][r] = kMaskedS;
         }
 
-        // ---- running maximum and the tile's quantization scale
-        float mx = -INFINITY;
+        // ---- running maximum (on the integers: c > 0) and the tile's quantization scale
+        int part[4] = {kMaskedS, kMaskedS, kMaskedS, kMaskedS};
 #pragma unroll
         for (int T = 0; T < KT; ++T)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, __int_as_float(sacc[T][r]));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float ymax = c * (mx - kMagicF);
+            for (int r = 0; r < 16; ++r) part[r & 3] = max(part[r & 3], sacc[T][r]);
+        const float ymax = c * (float)xor32_max(max(max(part[0], part[1]), max(part[2], part[3])));
         const float m_new = fmaxf(m, ymax);
-        float e = row_valid ? ymax - m_new : -INFINITY;
-#pragma unroll
-        for (int off = 16; off >= 1; off >>= 1) e = fmaxf(e, __shfl_xor(e, off));
+        // e = log2 of this wavefront's largest entry of Pt = max over its valid rows of
+        // (row maximum of the block - running maximum); always <= 0
+        float e = wave_max_nonpositive(row_valid ? ymax - m_new : -INFINITY);
         if constexpr (NW > 1) {
             if (lane == 0) tile_e[t & 1][w] = e;
         }
         __syncthreads();
+        if (t + 1 < cnt) lstore_v(next);
+        if (t + 2 < cnt) gload(t + 2);
         if constexpr (NW > 1) {
 #pragma unroll
             for (int ww = 0; ww < NW; ++ww) e = fmaxf(e, tile_e[t & 1][ww]);
@@ -235,9 +277,6 @@ __global__ __launch_bounds__(BLK * 2) void attn_i8_kernel(AttnArgs a) {
         const float s_p = __builtin_amdgcn_exp2f(e) * (1.0f / QMAXP);
         // exponent offset: X - m' - e + log2(qmaxP), so that the tile maximum maps to qmaxP
         const float off = LOG2_QMAXP - m_new - e;
-#ifdef PARO_FUSED_MAGIC
-        const float k0 = fmaf(-c, kMagicF, off);  // one fma per element, 2^-13 absolute in the exponent
-#endif
         m = m_new;
 
         // ---- E = qmaxP * 2^(X - m' - e); row sum; round half to even and pack as B operand
@@ -250,12 +289,7 @@ __global__ __launch_bounds__(BLK * 2) void attn_i8_kernel(AttnArgs a) {
                 unsigned pk = 0;
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
-                    const float f = __int_as_float(sacc[T][4 * qd + p]);
-#ifdef PARO_FUSED_MAGIC
-                    const float ev = __builtin_amdgcn_exp2f(fmaf(f, c, k0));
-#else
-                    const float ev = __builtin_amdgcn_exp2f(fmaf(f - kMagicF, c, off));
-#endif
+                    const float ev = __builtin_amdgcn_exp2f(fmaf((float)sacc[T][4 * qd + p], c, off));
                     rs += ev;
                     pk = __builtin_amdgcn_cvt_pk_u8_f32(ev, p, pk);  // round-half-even, saturating
                 }
@@ -264,8 +298,16 @@ __global__ __launch_bounds__(BLK * 2) void attn_i8_kernel(AttnArgs a) {
         }
         l = fmaf(l, alpha, rs * s_p);
 
-        // ---- O^T += V_j^T P^T
+        // ---- O^T = alpha * O^T + (sP sv_j) V_j^T P^T; the rescale is skipped when no running
+        // maximum in this wavefront moved (the common case once the row has seen its peak)
         const float sv_eff = s_p * svp[j] * (PVBITS == 4 ? 0.0625f : 1.0f);
+        const bool rescale = __builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0;
+        if (rescale) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[dt][r] *= alpha;
+        }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             v16i o;
@@ -277,10 +319,15 @@ __global__ __launch_bounds__(BLK * 2) void attn_i8_kernel(AttnArgs a) {
                 o = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf[T], o, 0, 0, 0);
             }
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[dt][r] = fmaf(acc[dt][r], alpha, sv_eff * (float)o[r]);
+            for (int r = 0; r < 16; ++r) acc[dt][r] = fmaf((float)o[r], sv_eff, acc[dt][r]);
         }
         stage = next;
-    }
+    };
+
+    const bool has_tail = (a.n_tokens % BLK) != 0 && cnt > 0 && col_of(cnt - 1) == a.kblocks - 1;
+    const int cnt_main = has_tail ? cnt - 1 : cnt;
+    for (int t = 0; t < cnt_main; ++t) step(std::false_type{}, t);
+    if (has_tail) step(std::true_type{}, cnt - 1);
 
     // ---- finalize: divide by the denominator, store the row (zeros for padded rows)
     const float l_tot = l + __shfl_xor(l, 32);
