@@ -81,7 +81,7 @@ def cpu_baseline(w, perm_ids, row_ptr, col_idx, target_seconds):
         vc, sv = po.prepare_operand(v, idx, w.npad, w.block, w.bits_pv)
         t1 = time.perf_counter()
         _ORACLE_CTX.update(qc=qc, sq=sq, kc=kc, sk=sk, vc=vc, sv=sv, N=w.N, block=w.block, row_ptr=row_ptr[h],
-                           col_idx=col_idx, qmax_p=None if w.bits_pv == 16 else po.qmax_of(w.bits_pv))
+                           col_idx=col_idx, qmax_p=None if w.bits_pv in (0, 16) else po.qmax_of(w.bits_pv))
         chunks = [list(range(c, w.k, cores)) for c in range(cores)]
         if cores > 1:
             with mp.get_context("fork").Pool(cores) as pool:  # forked after the context is set

@@ -265,11 +265,23 @@ def sparse_attention_head(
 # ---------------------------------------------------------------------------------------------
 # Whole path for one head, and for a problem
 # ---------------------------------------------------------------------------------------------
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Nearest bfloat16 (8 significand bits), ties to even, of float32 values; returned as float64."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    u = (u + np.uint32(0x7FFF) + lsb) & np.uint32(0xFFFF0000)
+    return u.view(np.float32).astype(np.float64)
+
+
 def prepare_operand(x: np.ndarray, idx: np.ndarray, npad: int, block: int, bits: int):
-    """permute + quantize one of Q/K/V of one head.  bits 16 = unquantized (scales of 1)."""
+    """permute + quantize one of Q/K/V of one head.
+    bits 8 / 4: integer codes and per-block scales; bits 16: the unquantized mode, operands held
+    in bfloat16 (scales of 1); bits 0: no rounding at all (exact reference arithmetic)."""
     xp = permute(x, idx, npad)
-    if bits == 16:
+    if bits == 0:
         return xp.astype(np.float64), np.ones(npad // block, np.float32)
+    if bits == 16:
+        return round_to_bf16(xp), np.ones(npad // block, np.float32)
     return quantize_blocks(xp, idx.shape[0], block, qmax_of(bits))
 
 
@@ -296,7 +308,7 @@ def paro_attention_head(
     qc, sq = prepare_operand(q, idx, npad, block, bits_qk)
     kc, sk = prepare_operand(k, idx, npad, block, bits_qk)
     vc, sv = prepare_operand(v, idx, npad, block, bits_pv)
-    qmax_p = None if bits_pv == 16 else qmax_of(bits_pv)
+    qmax_p = None if bits_pv in (0, 16) else qmax_of(bits_pv)
     op = sparse_attention_head(qc, sq, kc, sk, vc, sv, n, block, row_ptr, col_idx, qmax_p)
     return unpermute(op, idx)
 
@@ -308,10 +320,7 @@ def cast_output(o: np.ndarray, dtype: str) -> np.ndarray:
     if dtype == "f32":
         return o32.astype(np.float64)
     if dtype == "bf16":
-        u = o32.view(np.uint32)
-        lsb = (u >> np.uint32(16)) & np.uint32(1)
-        u = (u + np.uint32(0x7FFF) + lsb) & np.uint32(0xFFFF0000)
-        return u.view(np.float32).astype(np.float64)
+        return round_to_bf16(o32)
     raise ValueError(dtype)
 
 

@@ -33,8 +33,8 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def _compile(src: str, extra) -> str:
-    obj = os.path.join(LIBDIR, os.path.splitext(src)[0] + ".o")
+def _compile(src: str, extra, objdir: str = LIBDIR) -> str:
+    obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
     cmd = [hipcc(), *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
@@ -42,17 +42,19 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
-def build_library(extra_flags=(), verbose: bool = True) -> str:
-    os.makedirs(LIBDIR, exist_ok=True)
+def build_library(extra_flags=(), verbose: bool = True, out: str = LIBPATH) -> str:
+    """Compile every source and link ``out`` (default: the in-tree library the binding loads)."""
+    objdir = os.path.dirname(out)
+    os.makedirs(objdir, exist_ok=True)
     with ThreadPoolExecutor(max_workers=4) as ex:
-        objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
-    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIBPATH, *objs]
+        objs = list(ex.map(lambda s: _compile(s, list(extra_flags), objdir), SOURCES))
+    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
     if verbose:
-        print("built", LIBPATH)
-    return LIBPATH
+        print("built", out)
+    return out
 
 
 if __name__ == "__main__":

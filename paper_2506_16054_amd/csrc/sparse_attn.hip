@@ -341,6 +341,233 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
                    acc[dt][4 * qd + 3] * inv);
 }
 
+// -------------------------------------------------------------------------------------------
+// bf16 unquantized block-sparse mode (the sparse-only rows of the paper's tables): same work
+// split, transposed orientation, LDS ring and block list, on v_mfma_f32_32x32x16_bf16.  P is
+// not quantized, so there is no tile-wide scale and no cross-wavefront exchange; P enters the
+// PV product rounded to bf16 while the denominator accumulates it in fp32.
+// -------------------------------------------------------------------------------------------
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+template <int BLK, int D>
+struct Bf16Cfg {
+    static constexpr int KSTR = 2 * D + 16;    // bytes per K row in LDS (bf16 + 16 B pad)
+    static constexpr int VSTR = 2 * BLK + 16;  // bytes per V^T row in LDS
+    static constexpr int KBYTES = BLK * KSTR;
+    static constexpr int VBYTES = D * VSTR;
+    static constexpr int STAGE = KBYTES + VBYTES;
+    static constexpr int LDS_BYTES = 2 * STAGE;
+};
+
+template <int BLK, int D, typename OutT>
+__global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
+    using C = Bf16Cfg<BLK, D>;
+    constexpr int NW = BLK / 32;
+    constexpr int NT = 64 * NW;
+    constexpr int KSTR = C::KSTR, VSTR = C::VSTR, KBYTES = C::KBYTES, STAGE = C::STAGE;
+    constexpr int NKC = BLK * D * 2 / 16 / NT;  // 16-byte pieces of a K tile per thread
+    constexpr int NVC = NKC;
+    constexpr int KS = D / 16;    // contraction steps of QK^T (16 channels each)
+    constexpr int KT = BLK / 32;  // 32-key tiles per block
+    constexpr int DT = D / 32;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    const int wg = blockIdx.x;
+    const int logical = (wg & 7) * a.per_xcd + (wg >> 3);
+    if (logical >= a.total_wg) return;
+    const int bh = logical / a.kblocks;
+    const int i = logical - bh * a.kblocks;
+    const int h = bh % a.nh;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = tid >> 6;
+    const int n = lane & 31;
+    const int g = lane >> 5;
+
+    const int* rp = a.row_ptr + (size_t)h * (a.kblocks + 1) + i;
+    const int beg = min(max(rp[0], 0), a.nnz);
+    const int end = min(max(rp[1], beg), a.nnz);
+    const int cnt = end - beg;
+    const int* cols = a.col_idx + beg;
+
+    const size_t head_rows = (size_t)bh * a.kblocks * BLK;
+    const int row = i * BLK + 32 * w + n;
+    const bool row_valid = row < a.n_tokens;
+    const uint8_t* kbase = a.k + head_rows * D * 2;
+    const uint8_t* vbase = a.v + head_rows * D * 2;
+    const float c = a.qk_scale;
+
+    v8bf qf[KS];
+    {
+        const uint8_t* qrow = a.q + (head_rows + row) * D * 2 + 16 * g;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qf[s] = *(const v8bf*)(qrow + 32 * s);
+    }
+
+    v4i kreg[NKC], vreg[NVC];
+    auto col_of = [&](int t) { return min(max(cols[t], 0), a.kblocks - 1); };
+    auto gload = [&](int t) {
+        const int j = col_of(t);
+        const uint8_t* kp = kbase + (size_t)j * (BLK * D * 2);
+        const uint8_t* vp = vbase + (size_t)j * (BLK * D * 2);
+#pragma unroll
+        for (int cc = 0; cc < NKC; ++cc) kreg[cc] = *(const v4i*)(kp + 16 * (tid + NT * cc));
+#pragma unroll
+        for (int cc = 0; cc < NVC; ++cc) vreg[cc] = *(const v4i*)(vp + 16 * (tid + NT * cc));
+    };
+    auto lstore_k = [&](int stage) {
+        uint8_t* ks = lds + stage * STAGE;
+#pragma unroll
+        for (int cc = 0; cc < NKC; ++cc) {
+            const int o = 16 * (tid + NT * cc);
+            *(v4i*)(ks + (o / (2 * D)) * KSTR + (o % (2 * D))) = kreg[cc];
+        }
+    };
+    auto lstore_v = [&](int stage) {
+        uint8_t* vs = lds + stage * STAGE + KBYTES;
+#pragma unroll
+        for (int cc = 0; cc < NVC; ++cc) {
+            const int o = 16 * (tid + NT * cc);
+            *(v4i*)(vs + (o / (2 * BLK)) * VSTR + (o % (2 * BLK))) = vreg[cc];
+        }
+    };
+
+    float m = -INFINITY;
+    float l = 0.0f;
+    v16f acc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[dt][r] = 0.0f;
+
+    if (cnt > 0) {
+        gload(0);
+        lstore_k(0);
+        lstore_v(0);
+    }
+    if (cnt > 1) gload(1);
+    __syncthreads();
+
+    int stage = 0;
+    auto step = [&](auto tail_tag, int t) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
+        const int next = stage ^ 1;
+        if (t + 1 < cnt) lstore_k(next);
+        const uint8_t* ks = lds + stage * STAGE;
+        const uint8_t* vs = ks + KBYTES;
+
+        v16f sacc[KT];
+#pragma unroll
+        for (int T = 0; T < KT; ++T) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[T][r] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const v8bf kf = *(const v8bf*)(ks + (32 * T + n) * KSTR + 32 * s + 16 * g);
+                sacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[T], 0, 0, 0);
+            }
+        }
+        if constexpr (TAIL) {
+            const int nkeys = a.n_tokens - col_of(t) * BLK;
+#pragma unroll
+            for (int T = 0; T < KT; ++T)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (32 * T + 8 * (r >> 2) + 4 * g + (r & 3) >= nkeys) sacc[T][r] = -INFINITY;
+        }
+        float part[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+        for (int T = 0; T < KT; ++T)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) part[r & 3] = fmaxf(part[r & 3], sacc[T][r]);
+        float mx = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+        {
+            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_int(mx), __float_as_int(mx), false, false);
+            mx = fmaxf(__int_as_float((int)sw[0]), __int_as_float((int)sw[1]));
+        }
+        const float m_new = fmaxf(m, c * mx);
+        __syncthreads();
+        if (t + 1 < cnt) lstore_v(next);
+        if (t + 2 < cnt) gload(t + 2);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        m = m_new;
+
+        float rs = 0.0f;
+        v8bf pf[KT][2];
+#pragma unroll
+        for (int T = 0; T < KT; ++T)
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[T][8 * u + 2 * e2], c, -m_new));
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[T][8 * u + 2 * e2 + 1], c, -m_new));
+                    rs += p0 + p1;
+                    const v2bf pb = __builtin_convertvector(v2f{p0, p1}, v2bf);
+                    pf[T][u][2 * e2] = pb[0];
+                    pf[T][u][2 * e2 + 1] = pb[1];
+                }
+        l = fmaf(l, alpha, rs);
+
+        const bool rescale = __builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0;
+        if (rescale) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[dt][r] *= alpha;
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int T = 0; T < KT; ++T)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const v8bf vf = *(const v8bf*)(vs + (32 * dt + n) * VSTR + 2 * (32 * T + 16 * g + 8 * u));
+                    acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[T][u], acc[dt], 0, 0, 0);
+                }
+        stage = next;
+    };
+
+    const bool has_tail = (a.n_tokens % BLK) != 0 && cnt > 0 && col_of(cnt - 1) == a.kblocks - 1;
+    const int cnt_main = has_tail ? cnt - 1 : cnt;
+    for (int t = 0; t < cnt_main; ++t) step(std::false_type{}, t);
+    if (has_tail) step(std::true_type{}, cnt - 1);
+
+    const float l_tot = l + __shfl_xor(l, 32);
+    const float inv = (row_valid && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
+    OutT* orow = (OutT*)a.op + (head_rows + row) * D + 4 * g;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd)
+            store4(orow + 32 * dt + 8 * qd, acc[dt][4 * qd] * inv, acc[dt][4 * qd + 1] * inv, acc[dt][4 * qd + 2] * inv,
+                   acc[dt][4 * qd + 3] * inv);
+}
+
+template <int BLK, int D, typename OutT>
+static int launch_bf16_t(const AttnArgs& a, hipStream_t st) {
+    constexpr int bytes = Bf16Cfg<BLK, D>::LDS_BYTES;
+    static bool configured = false;  // raising the dynamic LDS limit is a per-function, idempotent setting
+    if (bytes > 48 * 1024 && !configured) {
+        hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_kernel<BLK, D, OutT>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e != hipSuccess) return fail(PARO_EHIP, "hipFuncSetAttribute(%d bytes of LDS): %s", bytes, hipGetErrorString(e));
+        configured = true;
+    }
+    hipLaunchKernelGGL((attn_bf16_kernel<BLK, D, OutT>), dim3((unsigned)(a.per_xcd * 8)), dim3(BLK * 2), bytes, st, a);
+    return PARO_OK;
+}
+
+template <typename OutT>
+static int launch_bf16(int blk, int d, const AttnArgs& a, hipStream_t st) {
+    if (blk == 64 && d == 64) return launch_bf16_t<64, 64, OutT>(a, st);
+    if (blk == 64 && d == 128) return launch_bf16_t<64, 128, OutT>(a, st);
+    if (blk == 32 && d == 64) return launch_bf16_t<32, 64, OutT>(a, st);
+    return launch_bf16_t<32, 128, OutT>(a, st);
+}
+
 template <int BLK, int D, int PVBITS>
 static void launch_out(paro_dtype out_dtype, const AttnArgs& a, hipStream_t st) {
     dim3 grid((unsigned)(a.per_xcd * 8));
@@ -378,7 +605,6 @@ extern "C" int paro_sparse_attn(const paro_shape* s, int bits_qk, int bits_pv, c
     if (nnz < 0 || nnz > 0x7fffffffLL) return fail(PARO_EINVAL, "nnz=%lld out of range", (long long)nnz);
     if (nnz > 0 && !col_idx) return fail(PARO_EINVAL, "col_idx is NULL but nnz=%lld", (long long)nnz);
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)op) & 15) return fail(PARO_EINVAL, "q, k, v and op must be 16-byte aligned");
-    if (b16) return fail(PARO_EUNSUPPORTED, "the bf16 mode is not built yet");
 
     AttnArgs a;
     a.q = (const uint8_t*)q;
@@ -397,7 +623,14 @@ extern "C" int paro_sparse_attn(const paro_shape* s, int bits_qk, int bits_pv, c
     a.total_wg = (int)((int64_t)s->B * s->nh * kb);
     a.per_xcd = (a.total_wg + 7) / 8;
     a.qk_scale = (float)(1.4426950408889634 / sqrt((double)s->d));
-    if (bits_pv == 8) launch_i8<8>(s->block, s->d, out_dtype, a, (hipStream_t)stream);
-    else launch_i8<4>(s->block, s->d, out_dtype, a, (hipStream_t)stream);
+    if (b16) {
+        const int st = out_dtype == PARO_F32 ? launch_bf16<float>(s->block, s->d, a, (hipStream_t)stream)
+                                             : launch_bf16<uint16_t>(s->block, s->d, a, (hipStream_t)stream);
+        if (st) return st;
+    } else if (bits_pv == 8) {
+        launch_i8<8>(s->block, s->d, out_dtype, a, (hipStream_t)stream);
+    } else {
+        launch_i8<4>(s->block, s->d, out_dtype, a, (hipStream_t)stream);
+    }
     return check_launch("paro_sparse_attn");
 }

@@ -42,8 +42,11 @@ class ParoAttention:
         s = self.s
         for src, xp in zip((q, k, v), self.xp):
             pb.paro_permute(s, self.perm_ids, src, xp)
-        pb.paro_quantize(s, self.bits_qk, pb.PARO_ROWS, self.xp[0], self.qc, self.sq)
-        pb.paro_quantize(s, self.bits_qk, pb.PARO_ROWS, self.xp[1], self.kc, self.sk)
+        if self.bits_qk == 16 and self.dtype == torch.bfloat16:
+            self.qc, self.kc = self.xp[0], self.xp[1]  # already bf16 rows: nothing to convert
+        else:
+            pb.paro_quantize(s, self.bits_qk, pb.PARO_ROWS, self.xp[0], self.qc, self.sq)
+            pb.paro_quantize(s, self.bits_qk, pb.PARO_ROWS, self.xp[1], self.kc, self.sk)
         pb.paro_quantize(s, self.bits_pv, pb.PARO_VT, self.xp[2], self.vc, self.sv)
 
     def attend(self) -> None:

@@ -29,7 +29,7 @@ def oracle_head(w, q, k, v, perm_id, row_ptr_h, col_idx, row_blocks=None):
     kc, sk = po.prepare_operand(k, idx, w.npad, w.block, w.bits_qk)
     vc, sv = po.prepare_operand(v, idx, w.npad, w.block, w.bits_pv)
     out.update(qc=qc, sq=sq, kc=kc, sk=sk, vc=vc, sv=sv)
-    qmax_p = None if w.bits_pv == 16 else po.qmax_of(w.bits_pv)
+    qmax_p = None if w.bits_pv in (0, 16) else po.qmax_of(w.bits_pv)
     diag = {}
     op = po.sparse_attention_head(qc, sq, kc, sk, vc, sv, w.N, w.block, row_ptr_h, col_idx, qmax_p, row_blocks,
                                   tie_tol=KERNEL_TIE_TOL, diag=diag)

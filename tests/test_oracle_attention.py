@@ -112,7 +112,7 @@ def test_full_path_dense_unquantized_is_order_invariant(perm_id):
     n = F * H * W + T
     q, k, v = (rng.standard_normal((n, d)) for _ in range(3))
     rp, ci = full_list(-(-n // block))
-    o = po.paro_attention_head(q, k, v, (F, H, W), T, perm_id, block, rp, ci, 16, 16)
+    o = po.paro_attention_head(q, k, v, (F, H, W), T, perm_id, block, rp, ci, 0, 0)
     assert o.shape == (n, d)
     assert np.allclose(o, sdpa_reference(q, k, v), rtol=0, atol=1e-12)
 
@@ -127,7 +127,7 @@ def test_full_path_mask_lives_in_reordered_coordinates():
     m = np.eye(n // block, dtype=bool)
     m[0, 2] = True
     rp, ci = list_from_mask(m)
-    o = po.paro_attention_head(q, k, v, (F, H, W), 0, 5, block, rp, ci, 16, 16)
+    o = po.paro_attention_head(q, k, v, (F, H, W), 0, 5, block, rp, ci, 0, 0)
     idx = np.arange(n).reshape(F, H, W).transpose(2, 1, 0).reshape(-1)  # WHF by numpy
     tm_new = token_mask_from_blocks(m, block, n)
     tm = np.zeros((n, n), bool)
@@ -310,3 +310,19 @@ def test_flip_risk_bounds_the_effect_of_a_rounding_tie():
     k2 = np.array([[0.0], [-0.3]])
     po.sparse_attention_head(q, ones, k2, ones, v, ones, n, block, rp, ci, 127, tie_tol=1e-9, diag=diag2)
     assert np.all(diag2["flip_risk"] == 0)
+
+
+def test_bf16_mode_rounds_operands_only():
+    # bits 16 = operands held in bfloat16, P and all accumulation exact: equals the exact masked
+    # softmax evaluated on bf16-rounded inputs (torch's bfloat16 cast is the independent rounding).
+    rng = np.random.default_rng(77)
+    F, H, W, d, block = 2, 4, 4, 8, 8
+    n = F * H * W
+    q, k, v = (rng.standard_normal((n, d)).astype(np.float32) for _ in range(3))
+    m = rand_mask(rng, n // block, 0.5)
+    rp, ci = list_from_mask(m)
+    o = po.paro_attention_head(q, k, v, (F, H, W), 0, 0, block, rp, ci, 16, 16)
+    qb, kb, vb = (torch.from_numpy(a).to(torch.bfloat16).to(torch.float64).numpy() for a in (q, k, v))
+    assert not np.array_equal(qb, q)
+    tm = token_mask_from_blocks(m, block, n)
+    assert np.allclose(o, brute_force(qb, kb, vb, tm), rtol=0, atol=1e-12)
