@@ -76,23 +76,30 @@ __device__ inline int xor32_max(int x) {
     return max((int)r[0], (int)r[1]);
 }
 
-// Maximum over the wavefront of values that are all <= 0 (or -inf), as a wave-uniform value.
-// Rows of 16 lanes are reduced with DPP (xor 1, xor 2, half mirror, mirror); the row results
-// are read through scalar registers.  For non-positive floats a larger value has the smaller
-// bit pattern, so the scalar combine is an unsigned minimum.
-__device__ inline float wave_max_nonpositive(float x) {
-    x = fmaxf(x, __int_as_float(dpp_mov<0xB1>(__float_as_int(x))));   // quad_perm [1,0,3,2]
-    x = fmaxf(x, __int_as_float(dpp_mov<0x4E>(__float_as_int(x))));   // quad_perm [2,3,0,1]
-    x = fmaxf(x, __int_as_float(dpp_mov<0x141>(__float_as_int(x))));  // row_half_mirror
-    x = fmaxf(x, __int_as_float(dpp_mov<0x140>(__float_as_int(x))));  // row_mirror
-    const unsigned b = (unsigned)__float_as_int(x);
-    const unsigned r0 = __builtin_amdgcn_readlane(b, 0), r1 = __builtin_amdgcn_readlane(b, 16);
-    const unsigned r2 = __builtin_amdgcn_readlane(b, 32), r3 = __builtin_amdgcn_readlane(b, 48);
-    return __uint_as_float(min(min(r0, r1), min(r2, r3)));
+// Minimum over the wavefront of unsigned values, as a wave-uniform value.  Rows of 16 lanes are
+// reduced with DPP (xor 1, xor 2, half mirror, mirror); the four row results are combined
+// through scalar registers.  Used on the bit patterns of floats that are all <= 0 (or -inf):
+// for those a larger value has the smaller bit pattern, so this is their maximum.
+__device__ inline unsigned wave_umin(unsigned x) {
+    x = min(x, (unsigned)dpp_mov<0xB1>((int)x));   // quad_perm [1,0,3,2]
+    x = min(x, (unsigned)dpp_mov<0x4E>((int)x));   // quad_perm [2,3,0,1]
+    x = min(x, (unsigned)dpp_mov<0x141>((int)x));  // row_half_mirror
+    x = min(x, (unsigned)dpp_mov<0x140>((int)x));  // row_mirror
+    const unsigned r0 = __builtin_amdgcn_readlane(x, 0), r1 = __builtin_amdgcn_readlane(x, 16);
+    const unsigned r2 = __builtin_amdgcn_readlane(x, 32), r3 = __builtin_amdgcn_readlane(x, 48);
+    return min(min(r0, r1), min(r2, r3));
 }
 
+// Integer matrix results become floats without a convert instruction: every accumulator chain
+// starts at the bit pattern of 1.5 * 2^23, so the register read as a float is 1.5 * 2^23 + result
+// exactly (|result| <= 127*127*128 < 2^22) and one subtraction on the full-rate fp32 pipe
+// recovers the result, bit-identical to v_cvt_f32_i32.
+constexpr int kAccBiasI = 0x4B400000;
+constexpr float kAccBiasF = 12582912.0f;
+__device__ inline float int_result(int raw) { return __int_as_float(raw) - kAccBiasF; }
+
 #ifndef PARO_ATTN_WAVES_D64
-#define PARO_ATTN_WAVES_D64 4  // wavefronts per SIMD the register allocation must allow, d = 64
+#define PARO_ATTN_WAVES_D64 3  // wavefronts per SIMD the register allocation must allow, d = 64
 #endif
 
 template <int BLK, int D, int PVBITS, typename OutT>
@@ -115,7 +122,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     static_assert(NKC >= 1 && NVC >= 1, "tile too small for the workgroup");
 
     __shared__ __attribute__((aligned(16))) uint8_t lds[2 * STAGE];
-    __shared__ float tile_e[2][NW];
+    __shared__ unsigned tile_e[2][NW];
 
     // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of
     // (head, row block) so the K/V of the heads it works on stay in its own L2.
@@ -154,12 +161,26 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
         for (int s = 0; s < KS; ++s) qf[s] = *(const v4i*)(qrow + 32 * s);
     }
 
+    // Column indices of the live list are fetched 64 at a time, one per lane, one chunk ahead;
+    // the column of block t is then a lane read, not a memory access on the per-block path.
+    auto load_cols = [&](int chunk) {
+        const int idx = min(chunk * 64 + lane, cnt - 1);
+        return cnt > 0 && chunk * 64 < cnt ? min(max(cols[idx], 0), a.kblocks - 1) : 0;
+    };
+    int cols_cur = load_cols(0), cols_nxt = load_cols(1);
+    int cur_chunk = 0;
+    auto col_of = [&](int t) {  // valid for t in chunk cur_chunk or cur_chunk + 1
+        return (t >> 6) == cur_chunk ? __builtin_amdgcn_readlane(cols_cur, t & 63) : __builtin_amdgcn_readlane(cols_nxt, t & 63);
+    };
+
     v4i kreg[NKC], vreg[NVC];
-    auto col_of = [&](int t) { return min(max(cols[t], 0), a.kblocks - 1); };
+    float sk_reg = 0.0f, sv_reg = 0.0f;  // scales of the block whose tiles sit in kreg / vreg
     auto gload = [&](int t) {
         const int j = col_of(t);
         const uint8_t* kp = kbase + (size_t)j * (BLK * D);
         const uint8_t* vp = vbase + (size_t)j * (BLK * D / VPACK);
+        sk_reg = skp[j];
+        sv_reg = svp[j];
 #pragma unroll
         for (int c = 0; c < NKC; ++c) kreg[c] = *(const v4i*)(kp + 16 * (tid + NT * c));
 #pragma unroll
@@ -202,16 +223,25 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[dt][r] = 0.0f;
 
+    // Start value of every integer accumulator chain, held in registers for the whole loop.
+    v16i acc_init;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc_init[r] = kAccBiasI;
+    asm volatile("" : "+v"(acc_init));  // opaque to the optimizer: not re-created per block
+
     // LDS ring of two stages, one barrier per live block (placed after the row maxima):
     //   K_{t+1} is stored at the top of iteration t  - every wavefront finished reading K_{t-1}
     //                                                  before barrier t-1;
     //   V_{t+1} is stored right after barrier t      - every wavefront finished reading V_{t-1}
     //                                                  before it arrived at barrier t;
     //   the registers are refilled from global memory (block t+2) after both stores.
+    float sk_cur = 0.0f, sv_cur = 0.0f;  // scales of block t
     if (cnt > 0) {
         gload(0);
         lstore_k(0);
         lstore_v(0);
+        sk_cur = sk_reg;
+        sv_cur = sv_reg;
     }
     if (cnt > 1) gload(1);
     __syncthreads();
@@ -225,26 +255,26 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
         const int next = stage ^ 1;
         if (t + 1 < cnt) lstore_k(next);
 
-        const int j = col_of(t);
-        const float c = sq_i * skp[j];
+        const float c = sq_i * sk_cur;
         const uint8_t* ks = lds + stage * STAGE;
         const uint8_t* vs = ks + KBYTES;
 
-        // ---- S^T = K_j Q_i^T (i32)
+        // ---- S^T = K_j Q_i^T (i32, biased)
         v16i sacc[KT];
 #pragma unroll
         for (int T = 0; T < KT; ++T) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[T][r] = 0;
+            sacc[T] = acc_init;
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 const v4i kf = *(const v4i*)(ks + (32 * T + n) * KSTR + 32 * s + 16 * g);
                 sacc[T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf[s], sacc[T], 0, 0, 0);
             }
         }
-        constexpr int kMaskedS = -(1 << 30);  // below any reachable sum; its exponential is 0
+        // Raw accumulator value of a masked logit: it loses every maximum, and read as a float
+        // it is +0, i.e. a logit of -1.5 * 2^23 * c whose exponential is 0.
+        constexpr int kMaskedS = 0;
         if constexpr (TAIL) {  // keys past N never receive probability mass
-            const int nkeys = a.n_tokens - j * BLK;
+            const int nkeys = a.n_tokens - (a.kblocks - 1) * BLK;
 #pragma unroll
             for (int T = 0; T < KT; ++T)
 #pragma unroll
@@ -252,27 +282,34 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
                     if (32 * T + 8 * (r >> 2) + 4 * g + (r & 3) >= nkeys) sacc[T][r] = kMaskedS;
         }
 
-        // ---- running maximum (on the integers: c > 0) and the tile's quantization scale
+        // ---- running maximum (on the raw integers: c > 0) and the tile's quantization scale
         int part[4] = {kMaskedS, kMaskedS, kMaskedS, kMaskedS};
 #pragma unroll
         for (int T = 0; T < KT; ++T)
 #pragma unroll
             for (int r = 0; r < 16; ++r) part[r & 3] = max(part[r & 3], sacc[T][r]);
-        const float ymax = c * (float)xor32_max(max(max(part[0], part[1]), max(part[2], part[3])));
+        const float ymax = c * (float)(xor32_max(max(max(part[0], part[1]), max(part[2], part[3]))) - kAccBiasI);
         const float m_new = fmaxf(m, ymax);
-        // e = log2 of this wavefront's largest entry of Pt = max over its valid rows of
-        // (row maximum of the block - running maximum); always <= 0
-        float e = wave_max_nonpositive(row_valid ? ymax - m_new : -INFINITY);
+        // e = log2 of the largest entry of the Pt tile = max over valid rows of (row maximum of
+        // the block - running maximum), always <= 0; reduced as an unsigned minimum of bit patterns
+        unsigned eb = wave_umin(row_valid ? __float_as_uint(ymax - m_new) : 0xFF800000u);
         if constexpr (NW > 1) {
-            if (lane == 0) tile_e[t & 1][w] = e;
+            if (lane == 0) tile_e[t & 1][w] = eb;
         }
         __syncthreads();
+        const float sk_next = sk_reg, sv_next = sv_reg;  // scales of block t+1, fetched with its tiles
         if (t + 1 < cnt) lstore_v(next);
+        if (((t + 2) & 63) == 0) {  // block t+2 opens a new chunk of 64 column indices
+            cols_cur = cols_nxt;
+            ++cur_chunk;
+            cols_nxt = load_cols(cur_chunk + 1);
+        }
         if (t + 2 < cnt) gload(t + 2);
         if constexpr (NW > 1) {
 #pragma unroll
-            for (int ww = 0; ww < NW; ++ww) e = fmaxf(e, tile_e[t & 1][ww]);
+            for (int ww = 0; ww < NW; ++ww) eb = min(eb, tile_e[t & 1][ww]);
         }
+        const float e = __uint_as_float(eb);
         const float alpha = __builtin_amdgcn_exp2f(m - m_new);
         const float s_p = __builtin_amdgcn_exp2f(e) * (1.0f / QMAXP);
         // exponent offset: X - m' - e + log2(qmaxP), so that the tile maximum maps to qmaxP
@@ -289,7 +326,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
                 unsigned pk = 0;
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
-                    const float ev = __builtin_amdgcn_exp2f(fmaf((float)sacc[T][4 * qd + p], c, off));
+                    const float ev = __builtin_amdgcn_exp2f(fmaf(int_result(sacc[T][4 * qd + p]), c, off));
                     rs += ev;
                     pk = __builtin_amdgcn_cvt_pk_u8_f32(ev, p, pk);  // round-half-even, saturating
                 }
@@ -300,7 +337,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 
         // ---- O^T = alpha * O^T + (sP sv_j) V_j^T P^T; the rescale is skipped when no running
         // maximum in this wavefront moved (the common case once the row has seen its peak)
-        const float sv_eff = s_p * svp[j] * (PVBITS == 4 ? 0.0625f : 1.0f);
+        const float sv_eff = s_p * sv_cur * (PVBITS == 4 ? 0.0625f : 1.0f);
         const bool rescale = __builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0;
         if (rescale) {
 #pragma unroll
@@ -310,21 +347,23 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
         }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-            v16i o;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[r] = 0;
+            v16i o = acc_init;
 #pragma unroll
             for (int T = 0; T < KT; ++T) {
                 const v4i vf = *(const v4i*)(vs + (32 * dt + n) * VSTR + 32 * T + 16 * g);
                 o = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf[T], o, 0, 0, 0);
             }
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[dt][r] = fmaf((float)o[r], sv_eff, acc[dt][r]);
+            for (int r = 0; r < 16; ++r) acc[dt][r] = fmaf(int_result(o[r]), sv_eff, acc[dt][r]);
         }
+        sk_cur = sk_next;
+        sv_cur = sv_next;
         stage = next;
     };
 
-    const bool has_tail = (a.n_tokens % BLK) != 0 && cnt > 0 && col_of(cnt - 1) == a.kblocks - 1;
+    // col_of(cnt - 1) is only addressable while its chunk is current, so the ragged-tail test
+    // reads the list directly (once per workgroup).
+    const bool has_tail = (a.n_tokens % BLK) != 0 && cnt > 0 && min(max(cols[cnt - 1], 0), a.kblocks - 1) == a.kblocks - 1;
     const int cnt_main = has_tail ? cnt - 1 : cnt;
     for (int t = 0; t < cnt_main; ++t) step(std::false_type{}, t);
     if (has_tail) step(std::true_type{}, cnt - 1);
