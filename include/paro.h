@@ -153,6 +153,30 @@ int paro_sparse_attn(const paro_shape* s, int bits_qk, int bits_pv, const void* 
                      const int32_t* row_ptr, const int32_t* col_idx, int64_t nnz,
                      paro_dtype out_dtype, void* op, void* stream);
 
+/* ---- fused forms (Sec. 4.1 "Minimize Hardware Overhead"; App. C "Overhead of Permutation") ----
+ * The paper removes the cost of the reorder by folding it into neighbouring kernels, so that
+ * only read / write-back addresses change.  These two entry points do that at both ends of the
+ * path; results are bit-identical to the unfused calls they replace. */
+
+/* paro_permute followed by paro_quantize without the intermediate tensor: the reorder happens
+ * in the load addresses of the quantizer.
+ *   h_perm_ids  host, [nh], values 0..5
+ *   x           [B,nh,N,d] dtype, default token order
+ *   codes, scales, bits, layout: exactly as paro_quantize produces them from the reordered tensor */
+int paro_permute_quantize(const paro_shape* s, paro_dtype dtype, int bits, paro_layout layout,
+                          const uint8_t* h_perm_ids, const void* x, void* codes, float* scales,
+                          void* stream);
+
+/* paro_sparse_attn followed by paro_unpermute without the intermediate tensor: row n' of the
+ * result is stored at row idx_h[n'] of o.  Arguments as paro_sparse_attn, plus
+ *   h_perm_ids  host, [nh], values 0..5
+ *   o           [B,nh,N,d] out_dtype, default token order (padded rows are not stored) */
+int paro_sparse_attn_unpermuted(const paro_shape* s, int bits_qk, int bits_pv, const void* q,
+                                const float* sq, const void* k, const float* sk, const void* v,
+                                const float* sv, const int32_t* row_ptr, const int32_t* col_idx,
+                                int64_t nnz, const uint8_t* h_perm_ids, paro_dtype out_dtype, void* o,
+                                void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,7 +27,7 @@ LIBPATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libpa
 EXPORTS = (
     "paro_version", "paro_strerror", "paro_last_error", "paro_ntokens", "paro_nblocks", "paro_npad",
     "paro_perm_index", "paro_vt_slot", "paro_mask_to_blocklist", "paro_permute", "paro_unpermute",
-    "paro_quantize", "paro_sparse_attn",
+    "paro_quantize", "paro_sparse_attn", "paro_permute_quantize", "paro_sparse_attn_unpermuted",
 )
 
 
@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.paro_unpermute.argtypes = [sp, i32, vp, vp, vp, vp]
         L.paro_quantize.argtypes = [sp, i32, i32, i32, vp, vp, vp, vp]
         L.paro_sparse_attn.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, vp, vp]
+        L.paro_permute_quantize.argtypes = [sp, i32, i32, i32, vp, vp, vp, vp, vp]
+        L.paro_sparse_attn_unpermuted.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, i32, vp, vp]
         _lib = L
     return _lib
 
@@ -213,6 +215,40 @@ def paro_quantize(s: paro_shape, bits: int, layout: int, xp, codes, scales) -> N
     _require(codes, "codes", codes_shape(s, bits, layout), torch.bfloat16 if bits == 16 else torch.int8)
     _require(scales, "scales", (s.B, s.nh, paro_nblocks(s)), torch.float32)
     _check(lib().paro_quantize(ctypes.byref(s), _dtype_code(xp), int(bits), int(layout), _ptr(xp), _ptr(codes), _ptr(scales), _stream()))
+
+
+def paro_permute_quantize(s: paro_shape, bits: int, layout: int, perm_ids, x, codes, scales) -> None:
+    import torch
+
+    _require(x, "x", (s.B, s.nh, paro_ntokens(s), s.d))
+    _require(codes, "codes", codes_shape(s, bits, layout), torch.bfloat16 if bits == 16 else torch.int8)
+    _require(scales, "scales", (s.B, s.nh, paro_nblocks(s)), torch.float32)
+    p = _perm_bytes(s, perm_ids)
+    _check(lib().paro_permute_quantize(ctypes.byref(s), _dtype_code(x), int(bits), int(layout), p.ctypes.data, _ptr(x), _ptr(codes),
+                                       _ptr(scales), _stream()))
+
+
+def _attn_operands(s: paro_shape, bits_qk: int, bits_pv: int, q, sq, k, sk, v, sv, row_ptr, col_idx) -> None:
+    import torch
+
+    kb = paro_nblocks(s)
+    _require(q, "q", codes_shape(s, bits_qk, PARO_ROWS))
+    _require(k, "k", codes_shape(s, bits_qk, PARO_ROWS))
+    _require(v, "v", codes_shape(s, bits_pv, PARO_VT))
+    for name, t in (("sq", sq), ("sk", sk), ("sv", sv)):
+        if t is not None:
+            _require(t, name, (s.B, s.nh, kb), torch.float32)
+    _require(row_ptr, "row_ptr", (s.nh, kb + 1), torch.int32)
+    _require(col_idx, "col_idx", None, torch.int32)
+
+
+def paro_sparse_attn_unpermuted(s: paro_shape, bits_qk: int, bits_pv: int, q, sq, k, sk, v, sv, row_ptr, col_idx, perm_ids, o) -> None:
+    _attn_operands(s, bits_qk, bits_pv, q, sq, k, sk, v, sv, row_ptr, col_idx)
+    _require(o, "o", (s.B, s.nh, paro_ntokens(s), s.d))
+    p = _perm_bytes(s, perm_ids)
+    _check(lib().paro_sparse_attn_unpermuted(ctypes.byref(s), int(bits_qk), int(bits_pv), _ptr(q), _ptr(sq), _ptr(k), _ptr(sk), _ptr(v),
+                                             _ptr(sv), _ptr(row_ptr), _ptr(col_idx) if col_idx.numel() else None,
+                                             int(col_idx.numel()), p.ctypes.data, _dtype_code(o), _ptr(o), _stream()))
 
 
 def paro_sparse_attn(s: paro_shape, bits_qk: int, bits_pv: int, q, sq, k, sk, v, sv, row_ptr, col_idx, op) -> None:

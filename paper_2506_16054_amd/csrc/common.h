@@ -33,6 +33,41 @@ __host__ __device__ inline AxisOrder axis_order(int perm_id) {
     }
 }
 
+// Everything a kernel needs to map a position of a head's reordered sequence to the position of
+// the same token in the default [F,H,W] order (and back), for all six axis orders at once.
+struct ReorderTable {
+    int n_tokens;   // N
+    int n_img;      // F*Hg*Wg; tokens at or beyond it are text and keep their place
+    int Hg, Wg;
+    int fwd[6][5];  // per axis order: extents of the middle and fastest axis, then the default-order
+                    // stride of the slowest, middle and fastest axis
+    int inv[6][3];  // per axis order: multiplier of the f, h and w coordinate in the reordered position
+    uint8_t perm[kMaxHeads];
+};
+
+// Fills `t` from the shape and the per-head order ids (host pointer); rejects ids above 5.
+int make_reorder_table(const paro_shape* s, const uint8_t* h_perm_ids, ReorderTable* t);
+
+// Default-order position of the token that sits at position n_new of head `head`'s sequence.
+__device__ inline int reorder_source(const ReorderTable& t, int head, int n_new) {
+    if (n_new >= t.n_img) return n_new;
+    const int* f = t.fwd[t.perm[head]];
+    const int c2 = n_new % f[1];
+    const int q = n_new / f[1];
+    const int c1 = q % f[0];
+    const int c0 = q / f[0];
+    return c0 * f[2] + c1 * f[3] + c2 * f[4];
+}
+
+// Position in head `head`'s reordered sequence of the token at default-order position n.
+__device__ inline int reorder_dest(const ReorderTable& t, int head, int n) {
+    if (n >= t.n_img) return n;
+    const int* mul = t.inv[t.perm[head]];
+    const int w = n % t.Wg;
+    const int q = n / t.Wg;
+    return (q / t.Hg) * mul[0] + (q % t.Hg) * mul[1] + w * mul[2];
+}
+
 // Slot of token i of a block in the PARO_VT layout: inside every run of 32 tokens the index
 // bits [q1 q0 g p1 p0] are stored as [g q1 q0 p1 p0].  A lane of the 32x32 matrix instruction
 // that produced S^T holds, for one query, the keys 8q + 4g + p (q, p = 0..3) of each 32-key

@@ -38,6 +38,30 @@ int check_shape(const paro_shape* s, int64_t* n_tokens, int64_t* k_blocks) {
     return PARO_OK;
 }
 
+int make_reorder_table(const paro_shape* s, const uint8_t* h_perm_ids, ReorderTable* t) {
+    if (!h_perm_ids) return fail(PARO_EINVAL, "perm_ids is NULL");
+    for (int h = 0; h < s->nh; ++h) {
+        if (h_perm_ids[h] > 5) return fail(PARO_EINVAL, "perm_ids[%d]=%d not in 0..5", h, (int)h_perm_ids[h]);
+        t->perm[h] = h_perm_ids[h];
+    }
+    t->n_img = s->F * s->Hg * s->Wg;
+    t->n_tokens = t->n_img + s->T_text;
+    t->Hg = s->Hg;
+    t->Wg = s->Wg;
+    const int dims[3] = {s->F, s->Hg, s->Wg};
+    const int stride[3] = {s->Hg * s->Wg, s->Wg, 1};
+    for (int p = 0; p < 6; ++p) {
+        const AxisOrder o = axis_order(p);
+        t->fwd[p][0] = dims[o.a[1]];
+        t->fwd[p][1] = dims[o.a[2]];
+        for (int i = 0; i < 3; ++i) t->fwd[p][2 + i] = stride[o.a[i]];
+        t->inv[p][o.a[0]] = dims[o.a[1]] * dims[o.a[2]];
+        t->inv[p][o.a[1]] = dims[o.a[2]];
+        t->inv[p][o.a[2]] = 1;
+    }
+    return PARO_OK;
+}
+
 int check_launch(const char* what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(PARO_EHIP, "%s: %s", what, hipGetErrorString(e));

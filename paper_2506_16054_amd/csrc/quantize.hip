@@ -8,6 +8,7 @@
 // LDS.  For the PARO_VT layout the codes are transposed through LDS so that the global stores
 // stay 16 bytes per lane and contiguous.
 #include <hip/hip_bf16.h>
+#include <string.h>
 
 #include "common.h"
 
@@ -46,9 +47,14 @@ __device__ inline float wave_max(float v) {
     return v;
 }
 
-template <typename InT, int BLK, int D, int BITS, int LAYOUT>
+// GATHER = false: the input is the reordered, padded tensor xp [bh][Npad][D].
+// GATHER = true : the input is x [bh][N][D] in the default token order and the reorder of
+//                 Sec. 4.1 happens on the way in (row n' of the group reads row idx(n') of x), so
+//                 the reordered tensor never exists in memory.
+template <typename InT, int BLK, int D, int BITS, int LAYOUT, bool GATHER>
 __global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ xp, uint8_t* __restrict__ codes,
-                                                       float* __restrict__ scales, int n_tokens, int kblocks) {
+                                                       float* __restrict__ scales, int n_tokens, int kblocks,
+                                                       ReorderTable table, int nh) {
     constexpr int ELEMS = BLK * D;
     constexpr int CHUNKS = ELEMS / 8;  // 8 consecutive channels of one token per chunk
     constexpr int IT = (CHUNKS + 255) / 256;
@@ -63,8 +69,15 @@ __global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ x
     const int bh = blockIdx.y;
     const int tid = threadIdx.x;
     const size_t group = (size_t)bh * kblocks + blk;
-    const InT* tile = xp + group * ELEMS;
+    const InT* tile = GATHER ? xp + (size_t)bh * n_tokens * D : xp + group * ELEMS;
     uint8_t* out = codes + group * OUT_BYTES;
+
+    // source row of every token of the group, computed once per row rather than once per chunk
+    __shared__ int src_row[GATHER ? BLK : 1];
+    if constexpr (GATHER) {
+        if (tid < BLK) src_row[tid] = blk * BLK + tid < n_tokens ? reorder_source(table, bh % nh, blk * BLK + tid) : 0;
+        __syncthreads();
+    }
 
     float x[IT][8];
     float amax = 0.0f;
@@ -74,7 +87,11 @@ __global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ x
         const int row = (chunk * 8) / D;
         const bool live = chunk < CHUNKS && blk * BLK + row < n_tokens;
         if (live) {
-            load8<InT>(tile + (size_t)chunk * 8, x[it]);
+            if constexpr (GATHER) {
+                load8<InT>(tile + (size_t)src_row[row] * D + (chunk * 8) % D, x[it]);
+            } else {
+                load8<InT>(tile + (size_t)chunk * 8, x[it]);
+            }
         } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e) x[it][e] = 0.0f;
@@ -155,48 +172,87 @@ __global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ x
     }
 }
 
-template <typename InT, int BLK, int D, int BITS>
-static void launch_layout(paro_layout layout, dim3 grid, hipStream_t st, const void* xp, void* codes, float* scales, int n, int k) {
-    if (layout == PARO_ROWS)
-        hipLaunchKernelGGL((quantize_kernel<InT, BLK, D, BITS, PARO_ROWS>), grid, dim3(256), 0, st, (const InT*)xp, (uint8_t*)codes, scales, n, k);
+struct QuantLaunch {
+    dim3 grid;
+    hipStream_t stream;
+    const void* in;
+    void* codes;
+    float* scales;
+    int n, k, nh;
+    bool gather;
+    ReorderTable table;
+};
+
+template <typename InT, int BLK, int D, int BITS, int LAYOUT>
+static void launch_gather(const QuantLaunch& q) {
+    if (q.gather)
+        hipLaunchKernelGGL((quantize_kernel<InT, BLK, D, BITS, LAYOUT, true>), q.grid, dim3(256), 0, q.stream, (const InT*)q.in,
+                           (uint8_t*)q.codes, q.scales, q.n, q.k, q.table, q.nh);
     else
-        hipLaunchKernelGGL((quantize_kernel<InT, BLK, D, BITS, PARO_VT>), grid, dim3(256), 0, st, (const InT*)xp, (uint8_t*)codes, scales, n, k);
+        hipLaunchKernelGGL((quantize_kernel<InT, BLK, D, BITS, LAYOUT, false>), q.grid, dim3(256), 0, q.stream, (const InT*)q.in,
+                           (uint8_t*)q.codes, q.scales, q.n, q.k, q.table, q.nh);
+}
+
+template <typename InT, int BLK, int D, int BITS>
+static void launch_layout(paro_layout layout, const QuantLaunch& q) {
+    if (layout == PARO_ROWS) launch_gather<InT, BLK, D, BITS, PARO_ROWS>(q);
+    else launch_gather<InT, BLK, D, BITS, PARO_VT>(q);
 }
 
 template <typename InT, int BLK, int D>
-static void launch_bits(int bits, paro_layout layout, dim3 grid, hipStream_t st, const void* xp, void* codes, float* scales, int n, int k) {
-    if (bits == 8) launch_layout<InT, BLK, D, 8>(layout, grid, st, xp, codes, scales, n, k);
-    else if (bits == 4) launch_layout<InT, BLK, D, 4>(layout, grid, st, xp, codes, scales, n, k);
-    else launch_layout<InT, BLK, D, 16>(layout, grid, st, xp, codes, scales, n, k);
+static void launch_bits(int bits, paro_layout layout, const QuantLaunch& q) {
+    if (bits == 8) launch_layout<InT, BLK, D, 8>(layout, q);
+    else if (bits == 4) launch_layout<InT, BLK, D, 4>(layout, q);
+    else launch_layout<InT, BLK, D, 16>(layout, q);
 }
 
 template <typename InT>
-static void launch_shape(int blk, int d, int bits, paro_layout layout, dim3 grid, hipStream_t st, const void* xp, void* codes,
-                         float* scales, int n, int k) {
-    if (blk == 64 && d == 64) launch_bits<InT, 64, 64>(bits, layout, grid, st, xp, codes, scales, n, k);
-    else if (blk == 64 && d == 128) launch_bits<InT, 64, 128>(bits, layout, grid, st, xp, codes, scales, n, k);
-    else if (blk == 32 && d == 64) launch_bits<InT, 32, 64>(bits, layout, grid, st, xp, codes, scales, n, k);
-    else launch_bits<InT, 32, 128>(bits, layout, grid, st, xp, codes, scales, n, k);
+static void launch_shape(int blk, int d, int bits, paro_layout layout, const QuantLaunch& q) {
+    if (blk == 64 && d == 64) launch_bits<InT, 64, 64>(bits, layout, q);
+    else if (blk == 64 && d == 128) launch_bits<InT, 64, 128>(bits, layout, q);
+    else if (blk == 32 && d == 64) launch_bits<InT, 32, 64>(bits, layout, q);
+    else launch_bits<InT, 32, 128>(bits, layout, q);
+}
+
+static int quantize_entry(const char* what, const paro_shape* s, paro_dtype dtype, int bits, paro_layout layout,
+                          const uint8_t* h_perm_ids, const void* in, void* codes, float* scales, void* stream) {
+    int64_t n, k;
+    if (int st = check_shape(s, &n, &k)) return st;
+    if (dtype != PARO_F32 && dtype != PARO_BF16) return fail(PARO_EINVAL, "dtype=%d is not a paro_dtype", (int)dtype);
+    if (bits != 8 && bits != 4 && bits != 16) return fail(PARO_EINVAL, "bits=%d: expected 8, 4 or 16", bits);
+    if (layout != PARO_ROWS && layout != PARO_VT) return fail(PARO_EINVAL, "layout=%d is not a paro_layout", (int)layout);
+    if (!in || !codes || !scales) return fail(PARO_EINVAL, "input, codes and scales must not be NULL");
+    if (((uintptr_t)in | (uintptr_t)codes) & 15) return fail(PARO_EINVAL, "input and codes must be 16-byte aligned");
+    if (in == codes) return fail(PARO_EINVAL, "input and codes must not alias");
+    QuantLaunch q;
+    q.gather = h_perm_ids != nullptr;
+    if (q.gather) {
+        if (int st = make_reorder_table(s, h_perm_ids, &q.table)) return st;
+    } else {
+        memset(&q.table, 0, sizeof(q.table));
+    }
+    q.grid = dim3((unsigned)k, (unsigned)(s->B * s->nh));
+    q.stream = (hipStream_t)stream;
+    q.in = in;
+    q.codes = codes;
+    q.scales = scales;
+    q.n = (int)n;
+    q.k = (int)k;
+    q.nh = s->nh;
+    if (dtype == PARO_F32) launch_shape<float>(s->block, s->d, bits, layout, q);
+    else launch_shape<uint16_t>(s->block, s->d, bits, layout, q);
+    return check_launch(what);
 }
 
 }  // namespace paro
 
 extern "C" int paro_quantize(const paro_shape* s, paro_dtype dtype, int bits, paro_layout layout, const void* xp,
                              void* codes, float* scales, void* stream) {
-    using namespace paro;
-    int64_t n, k;
-    if (int st = check_shape(s, &n, &k)) return st;
-    if (dtype != PARO_F32 && dtype != PARO_BF16) return fail(PARO_EINVAL, "dtype=%d is not a paro_dtype", (int)dtype);
-    if (bits != 8 && bits != 4 && bits != 16) return fail(PARO_EINVAL, "bits=%d: expected 8, 4 or 16", bits);
-    if (layout != PARO_ROWS && layout != PARO_VT) return fail(PARO_EINVAL, "layout=%d is not a paro_layout", (int)layout);
-    if (!xp || !codes || !scales) return fail(PARO_EINVAL, "xp, codes and scales must not be NULL");
-    if (((uintptr_t)xp | (uintptr_t)codes) & 15) return fail(PARO_EINVAL, "xp and codes must be 16-byte aligned");
-    if (xp == codes) return fail(PARO_EINVAL, "xp and codes must not alias");
-    if (k > 65535 * 32768LL) return fail(PARO_EUNSUPPORTED, "too many blocks");
-    dim3 grid((unsigned)k, (unsigned)(s->B * s->nh));
-    if (dtype == PARO_F32)
-        launch_shape<float>(s->block, s->d, bits, layout, grid, (hipStream_t)stream, xp, codes, scales, (int)n, (int)k);
-    else
-        launch_shape<uint16_t>(s->block, s->d, bits, layout, grid, (hipStream_t)stream, xp, codes, scales, (int)n, (int)k);
-    return check_launch("paro_quantize");
+    return paro::quantize_entry("paro_quantize", s, dtype, bits, layout, nullptr, xp, codes, scales, stream);
+}
+
+extern "C" int paro_permute_quantize(const paro_shape* s, paro_dtype dtype, int bits, paro_layout layout,
+                                     const uint8_t* h_perm_ids, const void* x, void* codes, float* scales, void* stream) {
+    if (!h_perm_ids) return paro::fail(PARO_EINVAL, "perm_ids is NULL");
+    return paro::quantize_entry("paro_permute_quantize", s, dtype, bits, layout, h_perm_ids, x, codes, scales, stream);
 }

@@ -26,6 +26,8 @@
 //        which also packs four codes into one register,
 //   l  = l * 2^(m - m') + sP * rowsum(E),  sP = 2^e / qmaxP   (the P tile maximum over qmaxP)
 //   acc = acc * 2^(m - m') + (sP * sv_j) * float(Pc V_j)
+#include <string.h>
+
 #include <type_traits>
 
 #include "common.h"
@@ -52,7 +54,19 @@ struct AttnArgs {
     int total_wg;  // B * nh * kblocks
     int per_xcd;   // ceil(total_wg / 8)
     float qk_scale;  // log2(e) / sqrt(d)
+    int scatter;     // 1: store row n' of the result at row idx(n') of o [B,nh,N,d] (Sec. 4.1 inverse reorder
+                     //    done by adjusting the write-back address); 0: store op [B,nh,Npad,d]
+    ReorderTable table;
 };
+
+// Where this lane's query row goes: element offset of the row in the output tensor, or -1 if the
+// row is not stored (a padded row when the output is the unpadded, default-order tensor).
+template <int D>
+__device__ inline long long out_row_offset(const AttnArgs& a, int bh, int h, size_t head_rows, int row, bool row_valid) {
+    if (!a.scatter) return (long long)((head_rows + row) * D);
+    if (!row_valid) return -1;
+    return (long long)(((size_t)bh * a.n_tokens + reorder_source(a.table, h, row)) * D);
+}
 
 __device__ inline unsigned bf16_rne(float f) {
     const unsigned u = __float_as_uint(f);
@@ -371,13 +385,16 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     // ---- finalize: divide by the denominator, store the row (zeros for padded rows)
     const float l_tot = l + __shfl_xor(l, 32);
     const float inv = (row_valid && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
-    OutT* orow = (OutT*)a.op + (head_rows + row) * D + 4 * g;
+    const long long ooff = out_row_offset<D>(a, bh, h, head_rows, row, row_valid);
+    if (ooff >= 0) {
+        OutT* orow = (OutT*)a.op + ooff + 4 * g;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int qd = 0; qd < 4; ++qd)
-            store4(orow + 32 * dt + 8 * qd, acc[dt][4 * qd] * inv, acc[dt][4 * qd + 1] * inv, acc[dt][4 * qd + 2] * inv,
-                   acc[dt][4 * qd + 3] * inv);
+            for (int qd = 0; qd < 4; ++qd)
+                store4(orow + 32 * dt + 8 * qd, acc[dt][4 * qd] * inv, acc[dt][4 * qd + 1] * inv, acc[dt][4 * qd + 2] * inv,
+                       acc[dt][4 * qd + 3] * inv);
+    }
 }
 
 // -------------------------------------------------------------------------------------------
@@ -577,13 +594,16 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
 
     const float l_tot = l + __shfl_xor(l, 32);
     const float inv = (row_valid && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
-    OutT* orow = (OutT*)a.op + (head_rows + row) * D + 4 * g;
+    const long long ooff = out_row_offset<D>(a, bh, h, head_rows, row, row_valid);
+    if (ooff >= 0) {
+        OutT* orow = (OutT*)a.op + ooff + 4 * g;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int qd = 0; qd < 4; ++qd)
-            store4(orow + 32 * dt + 8 * qd, acc[dt][4 * qd] * inv, acc[dt][4 * qd + 1] * inv, acc[dt][4 * qd + 2] * inv,
-                   acc[dt][4 * qd + 3] * inv);
+            for (int qd = 0; qd < 4; ++qd)
+                store4(orow + 32 * dt + 8 * qd, acc[dt][4 * qd] * inv, acc[dt][4 * qd + 1] * inv, acc[dt][4 * qd + 2] * inv,
+                       acc[dt][4 * qd + 3] * inv);
+    }
 }
 
 template <int BLK, int D, typename OutT>
@@ -626,10 +646,10 @@ static void launch_i8(int blk, int d, paro_dtype out_dtype, const AttnArgs& a, h
 
 }  // namespace paro
 
-extern "C" int paro_sparse_attn(const paro_shape* s, int bits_qk, int bits_pv, const void* q, const float* sq, const void* k,
-                                const float* sk, const void* v, const float* sv, const int32_t* row_ptr,
-                                const int32_t* col_idx, int64_t nnz, paro_dtype out_dtype, void* op, void* stream) {
-    using namespace paro;
+namespace paro {
+static int attn_entry(const char* what, const paro_shape* s, int bits_qk, int bits_pv, const void* q, const float* sq, const void* k,
+                      const float* sk, const void* v, const float* sv, const int32_t* row_ptr, const int32_t* col_idx,
+                      int64_t nnz, const uint8_t* h_perm_ids, paro_dtype out_dtype, void* op, void* stream) {
     int64_t n, kb;
     if (int st = check_shape(s, &n, &kb)) return st;
     const bool i8 = bits_qk == 8 && (bits_pv == 8 || bits_pv == 4);
@@ -662,6 +682,12 @@ extern "C" int paro_sparse_attn(const paro_shape* s, int bits_qk, int bits_pv, c
     a.total_wg = (int)((int64_t)s->B * s->nh * kb);
     a.per_xcd = (a.total_wg + 7) / 8;
     a.qk_scale = (float)(1.4426950408889634 / sqrt((double)s->d));
+    a.scatter = h_perm_ids != nullptr;
+    if (a.scatter) {
+        if (int st = make_reorder_table(s, h_perm_ids, &a.table)) return st;
+    } else {
+        memset(&a.table, 0, sizeof(a.table));
+    }
     if (b16) {
         const int st = out_dtype == PARO_F32 ? launch_bf16<float>(s->block, s->d, a, (hipStream_t)stream)
                                              : launch_bf16<uint16_t>(s->block, s->d, a, (hipStream_t)stream);
@@ -671,5 +697,22 @@ extern "C" int paro_sparse_attn(const paro_shape* s, int bits_qk, int bits_pv, c
     } else {
         launch_i8<4>(s->block, s->d, out_dtype, a, (hipStream_t)stream);
     }
-    return check_launch("paro_sparse_attn");
+    return check_launch(what);
+}
+}  // namespace paro
+
+extern "C" int paro_sparse_attn(const paro_shape* s, int bits_qk, int bits_pv, const void* q, const float* sq, const void* k,
+                                const float* sk, const void* v, const float* sv, const int32_t* row_ptr,
+                                const int32_t* col_idx, int64_t nnz, paro_dtype out_dtype, void* op, void* stream) {
+    return paro::attn_entry("paro_sparse_attn", s, bits_qk, bits_pv, q, sq, k, sk, v, sv, row_ptr, col_idx, nnz, nullptr, out_dtype,
+                            op, stream);
+}
+
+extern "C" int paro_sparse_attn_unpermuted(const paro_shape* s, int bits_qk, int bits_pv, const void* q, const float* sq,
+                                           const void* k, const float* sk, const void* v, const float* sv,
+                                           const int32_t* row_ptr, const int32_t* col_idx, int64_t nnz,
+                                           const uint8_t* h_perm_ids, paro_dtype out_dtype, void* o, void* stream) {
+    if (!h_perm_ids) return paro::fail(PARO_EINVAL, "perm_ids is NULL");
+    return paro::attn_entry("paro_sparse_attn_unpermuted", s, bits_qk, bits_pv, q, sq, k, sk, v, sv, row_ptr, col_idx, nnz,
+                            h_perm_ids, out_dtype, o, stream);
 }

@@ -58,6 +58,34 @@ class ParoAttention:
         return self.o
 
     def run(self, q, k, v):
+        """The path as five separate steps (reorder, quantize, attention, inverse reorder)."""
         self.prepare(q, k, v)
         self.attend()
         return self.finish()
+
+    # ---- fused form: the reorder lives in the quantizer's load addresses and in the attention
+    # kernel's store addresses; four launches, no reordered intermediates
+    def _fused_buffers(self):
+        if not hasattr(self, "_fq"):
+            s, z = self.s, dict(device=self.dev)
+            ct = torch.bfloat16 if self.bits_qk == 16 else torch.int8
+            self._fq = torch.empty(pb.codes_shape(s, self.bits_qk, pb.PARO_ROWS), dtype=ct, **z)
+            self._fk = torch.empty(pb.codes_shape(s, self.bits_qk, pb.PARO_ROWS), dtype=ct, **z)
+        return self._fq, self._fk
+
+    def prepare_fused(self, q, k, v) -> None:
+        s = self.s
+        fq, fk = self._fused_buffers()
+        pb.paro_permute_quantize(s, self.bits_qk, pb.PARO_ROWS, self.perm_ids, q, fq, self.sq)
+        pb.paro_permute_quantize(s, self.bits_qk, pb.PARO_ROWS, self.perm_ids, k, fk, self.sk)
+        pb.paro_permute_quantize(s, self.bits_pv, pb.PARO_VT, self.perm_ids, v, self.vc, self.sv)
+
+    def attend_fused(self):
+        fq, fk = self._fused_buffers()
+        pb.paro_sparse_attn_unpermuted(self.s, self.bits_qk, self.bits_pv, fq, self.sq, fk, self.sk, self.vc, self.sv,
+                                       self.row_ptr, self.col_idx, self.perm_ids, self.o)
+        return self.o
+
+    def run_fused(self, q, k, v):
+        self.prepare_fused(q, k, v)
+        return self.attend_fused()

@@ -258,3 +258,31 @@ def test_empty_row_block_gives_zeros():
     r = oracle_head(w, q[0, 0], k[0, 0], v[0, 0], 3, row_ptr[0], col_idx)
     assert np.all(op[128:192] == 0)
     check_attention(op, r["op"], r["flip_risk"], MAX_ABS, REL_L2)
+
+
+@pytest.mark.parametrize("name", ["video64", "video64_int4", "video32_f32", "flux128", "flux128_b32_int4", "video64_bf16", "video32_bf16_f32io"])
+def test_fused_entry_points_are_bit_identical_to_the_separate_steps(name):
+    """paro_permute_quantize == paro_permute + paro_quantize and paro_sparse_attn_unpermuted ==
+    paro_sparse_attn + paro_unpermute, bit for bit (so the oracle parity of the separate steps
+    carries over), including untouched padding and ragged tails."""
+    torch = _torch()
+    p = problem(name)
+    pa = p.pa
+    ref_q, ref_k, ref_v = pa.qc.clone(), pa.kc.clone(), pa.vc.clone()
+    ref_s = [t.clone() for t in (pa.sq, pa.sk, pa.sv)]
+    ref_o = p.o.clone()
+    for t in (pa.vc,):
+        t.zero_()
+    for t in (pa.sq, pa.sk, pa.sv):
+        t.fill_(float("nan"))
+    pa.o.fill_(float("nan"))
+    o = pa.run_fused(p.dq, p.dk, p.dv)
+    torch.cuda.synchronize()
+    fq, fk = pa._fused_buffers()
+    assert torch.equal(fq.view(torch.uint8) if fq.dtype == torch.int8 else fq, ref_q.view(torch.uint8) if ref_q.dtype == torch.int8 else ref_q)
+    assert torch.equal(fk.view(torch.uint8) if fk.dtype == torch.int8 else fk, ref_k.view(torch.uint8) if ref_k.dtype == torch.int8 else ref_k)
+    assert torch.equal(pa.vc, ref_v)
+    if p.w.bits_qk == 8:
+        for got, ref in zip((pa.sq, pa.sk, pa.sv), ref_s):
+            assert torch.equal(got, ref)
+    assert torch.equal(o, ref_o)
