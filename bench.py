@@ -27,6 +27,19 @@ PEAK_INT8_TOPS = 5000.0  # MI355X dense INT8 MFMA, published: 5.0 POP/s
 PEAK_BF16_TFLOPS = 2500.0
 
 
+def recorded_traffic(workload: str):
+    """HBM bytes per launch of the attention kernel, as recorded from the rocprofv3 FETCH_SIZE /
+    WRITE_SIZE runs summarised under profiles/ (None if no summary exists for this workload)."""
+    import re
+
+    path = os.path.join(ROOT, "profiles", "hot_path_%s_hbm_traffic.md" % workload)
+    try:
+        m = re.search(r"traffic_bytes_per_launch paro_sparse_attn %s = (\d+)" % re.escape(workload), open(path).read())
+        return int(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -187,6 +200,10 @@ def main():
     attn_avg = sum(attn_ms) / len(attn_ms)
 
     quantized = w.bits_qk == 8
+    # compulsory HBM bytes of one attention launch: Q, K, V operands read once, output written once
+    qk_bytes = 1 if quantized else 2
+    v_bytes = 0.5 if w.bits_pv == 4 else (1 if w.bits_pv == 8 else 2)
+    algorithmic_bytes = int(w.B * w.nh * w.npad * w.d * (2 * qk_bytes + v_bytes) + w.B * w.nh * w.N * w.d * (2 if w.dtype == "bf16" else 4))
     peak = PEAK_INT8_TOPS if quantized else PEAK_BF16_TFLOPS
     achieved = live_ops / (attn_avg * 1e-3) / 1e12
     out = {
@@ -223,7 +240,9 @@ def main():
             "peak": peak,
             "unit": "TOP/s" if quantized else "TFLOP/s",
             "frac": achieved / peak,
-            "traffic": None,
+            "traffic": recorded_traffic(w.name),
+            "traffic_unit": "bytes per launch (HBM read + write, rocprofv3 counters scaled by a known copy)",
+            "algorithmic_bytes": algorithmic_bytes,
         },
     }
     if cpu is not None:
