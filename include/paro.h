@@ -101,6 +101,16 @@ int paro_vt_slot(int block, int i);
 int paro_mask_to_blocklist(int nh, int k, const uint8_t* h_bitmask, int32_t* h_row_ptr,
                            int32_t* h_col_idx, int64_t cap, int64_t* nnz_out);
 
+/* Launch order of the row blocks for paro_sparse_attn (a performance hint, never a change of
+ * results).  Rows of a static mask differ widely in live blocks (Sec. 4.2 (3): one threshold per
+ * head), so the kernels can start the heaviest row blocks first.  h_order has B*nh*k entries;
+ * entry p is the row block (b*nh + h)*k + i that runs at launch position p.  Positions are dealt
+ * to the 8 XCDs in 8 contiguous ranges; inside a range, row blocks are sorted by descending live
+ * count within groups of consecutive heads whose K and V operands fit one L2 together (so the
+ * reordering never evicts the K/V tiles being reused).  bits_* size that footprint.  Host only. */
+int paro_schedule_rows(const paro_shape* s, int bits_qk, int bits_pv, const int32_t* h_row_ptr,
+                       int32_t* h_order);
+
 /* ---- device entry points ---------------------------------------------------------------- */
 
 /* Token reorder (Sec. 4.1): xp[b,h,n',:] = x[b,h,idx_h[n'],:], rows n' >= N of xp set to 0.
@@ -147,11 +157,14 @@ int paro_quantize(const paro_shape* s, paro_dtype dtype, int bits, paro_layout l
  *   row_ptr  int32 [nh][k+1], col_idx int32 [nnz]: DEVICE copies of the block list; entries
  *            outside [0,nnz] / [0,k) are clamped, so a corrupt list cannot address outside the
  *            operands (the result is then meaningless but the call is memory-safe)
+ *   row_order int32 [B*nh*k], DEVICE copy of paro_schedule_rows' output, or NULL for the natural
+ *            order; must be a permutation of 0..B*nh*k-1 (entries are clamped; a row block that
+ *            is missing from it is not computed, one that appears twice is computed twice)
  *   op       [B,nh,Npad,d] out_dtype; rows >= N are written as zeros */
 int paro_sparse_attn(const paro_shape* s, int bits_qk, int bits_pv, const void* q, const float* sq,
                      const void* k, const float* sk, const void* v, const float* sv,
                      const int32_t* row_ptr, const int32_t* col_idx, int64_t nnz,
-                     paro_dtype out_dtype, void* op, void* stream);
+                     const int32_t* row_order, paro_dtype out_dtype, void* op, void* stream);
 
 /* ---- fused forms (Sec. 4.1 "Minimize Hardware Overhead"; App. C "Overhead of Permutation") ----
  * The paper removes the cost of the reorder by folding it into neighbouring kernels, so that
@@ -174,8 +187,8 @@ int paro_permute_quantize(const paro_shape* s, paro_dtype dtype, int bits, paro_
 int paro_sparse_attn_unpermuted(const paro_shape* s, int bits_qk, int bits_pv, const void* q,
                                 const float* sq, const void* k, const float* sk, const void* v,
                                 const float* sv, const int32_t* row_ptr, const int32_t* col_idx,
-                                int64_t nnz, const uint8_t* h_perm_ids, paro_dtype out_dtype, void* o,
-                                void* stream);
+                                int64_t nnz, const int32_t* row_order, const uint8_t* h_perm_ids,
+                                paro_dtype out_dtype, void* o, void* stream);
 
 #ifdef __cplusplus
 }

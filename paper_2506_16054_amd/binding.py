@@ -27,7 +27,7 @@ LIBPATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libpa
 EXPORTS = (
     "paro_version", "paro_strerror", "paro_last_error", "paro_ntokens", "paro_nblocks", "paro_npad",
     "paro_perm_index", "paro_vt_slot", "paro_mask_to_blocklist", "paro_permute", "paro_unpermute",
-    "paro_quantize", "paro_sparse_attn", "paro_permute_quantize", "paro_sparse_attn_unpermuted",
+    "paro_quantize", "paro_sparse_attn", "paro_permute_quantize", "paro_sparse_attn_unpermuted", "paro_schedule_rows",
 )
 
 
@@ -66,9 +66,10 @@ def lib() -> ctypes.CDLL:
         L.paro_permute.argtypes = [sp, i32, vp, vp, vp, vp]
         L.paro_unpermute.argtypes = [sp, i32, vp, vp, vp, vp]
         L.paro_quantize.argtypes = [sp, i32, i32, i32, vp, vp, vp, vp]
-        L.paro_sparse_attn.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, vp, vp]
+        L.paro_sparse_attn.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, i32, vp, vp]
+        L.paro_schedule_rows.argtypes = [sp, i32, i32, vp, vp]
         L.paro_permute_quantize.argtypes = [sp, i32, i32, i32, vp, vp, vp, vp, vp]
-        L.paro_sparse_attn_unpermuted.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, i32, vp, vp]
+        L.paro_sparse_attn_unpermuted.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i32, vp, vp]
         _lib = L
     return _lib
 
@@ -173,6 +174,17 @@ def paro_mask_to_blocklist(nh: int, k: int, bitmask: np.ndarray) -> Tuple[np.nda
     return row_ptr, col_idx[: nnz.value]
 
 
+def paro_schedule_rows(s: paro_shape, bits_qk: int, bits_pv: int, row_ptr: np.ndarray) -> np.ndarray:
+    """Launch order of the row blocks (host): int32 [B*nh*k]."""
+    k = paro_nblocks(s)
+    rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    if rp.shape != (s.nh, k + 1):
+        raise ParoError(PARO_EINVAL, "row_ptr has shape %s, expected %s" % (rp.shape, (s.nh, k + 1)))
+    order = np.empty(s.B * s.nh * k, np.int32)
+    _check(lib().paro_schedule_rows(ctypes.byref(s), int(bits_qk), int(bits_pv), rp.ctypes.data, order.ctypes.data))
+    return order
+
+
 # ---------------------------------------------------------------------------------------------
 # device calls (torch tensors on the GPU; enqueued on torch's current stream)
 # ---------------------------------------------------------------------------------------------
@@ -242,16 +254,27 @@ def _attn_operands(s: paro_shape, bits_qk: int, bits_pv: int, q, sq, k, sk, v, s
     _require(col_idx, "col_idx", None, torch.int32)
 
 
-def paro_sparse_attn_unpermuted(s: paro_shape, bits_qk: int, bits_pv: int, q, sq, k, sk, v, sv, row_ptr, col_idx, perm_ids, o) -> None:
+def _order_ptr(s: paro_shape, row_order):
+    import torch
+
+    if row_order is None:
+        return None
+    _require(row_order, "row_order", (s.B * s.nh * paro_nblocks(s),), torch.int32)
+    return _ptr(row_order)
+
+
+def paro_sparse_attn_unpermuted(s: paro_shape, bits_qk: int, bits_pv: int, q, sq, k, sk, v, sv, row_ptr, col_idx, perm_ids, o,
+                                row_order=None) -> None:
     _attn_operands(s, bits_qk, bits_pv, q, sq, k, sk, v, sv, row_ptr, col_idx)
     _require(o, "o", (s.B, s.nh, paro_ntokens(s), s.d))
     p = _perm_bytes(s, perm_ids)
     _check(lib().paro_sparse_attn_unpermuted(ctypes.byref(s), int(bits_qk), int(bits_pv), _ptr(q), _ptr(sq), _ptr(k), _ptr(sk), _ptr(v),
                                              _ptr(sv), _ptr(row_ptr), _ptr(col_idx) if col_idx.numel() else None,
-                                             int(col_idx.numel()), p.ctypes.data, _dtype_code(o), _ptr(o), _stream()))
+                                             int(col_idx.numel()), _order_ptr(s, row_order), p.ctypes.data, _dtype_code(o), _ptr(o),
+                                             _stream()))
 
 
-def paro_sparse_attn(s: paro_shape, bits_qk: int, bits_pv: int, q, sq, k, sk, v, sv, row_ptr, col_idx, op) -> None:
+def paro_sparse_attn(s: paro_shape, bits_qk: int, bits_pv: int, q, sq, k, sk, v, sv, row_ptr, col_idx, op, row_order=None) -> None:
     import torch
 
     kb, npad = paro_nblocks(s), paro_npad(s)
@@ -266,4 +289,4 @@ def paro_sparse_attn(s: paro_shape, bits_qk: int, bits_pv: int, q, sq, k, sk, v,
     _require(op, "op", (s.B, s.nh, npad, s.d))
     _check(lib().paro_sparse_attn(ctypes.byref(s), int(bits_qk), int(bits_pv), _ptr(q), _ptr(sq), _ptr(k), _ptr(sk), _ptr(v),
                                   _ptr(sv), _ptr(row_ptr), _ptr(col_idx) if col_idx.numel() else None, int(col_idx.numel()),
-                                  _dtype_code(op), _ptr(op), _stream()))
+                                  _order_ptr(s, row_order), _dtype_code(op), _ptr(op), _stream()))

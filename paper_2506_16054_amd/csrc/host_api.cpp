@@ -4,6 +4,9 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
+#include <vector>
+
 #include "common.h"
 
 namespace paro {
@@ -156,6 +159,41 @@ int paro_mask_to_blocklist(int nh, int k, const uint8_t* h_bitmask, int32_t* h_r
     }
     *nnz_out = nnz;
     if (nnz > cap) return fail(PARO_EINVAL, "h_col_idx holds %lld entries but the mask has %lld live blocks", (long long)cap, (long long)nnz);
+    return PARO_OK;
+}
+
+int paro_schedule_rows(const paro_shape* s, int bits_qk, int bits_pv, const int32_t* h_row_ptr, int32_t* h_order) {
+    int64_t n, k;
+    if (int st = check_shape(s, &n, &k)) return st;
+    if (!h_row_ptr || !h_order) return fail(PARO_EINVAL, "h_row_ptr and h_order must not be NULL");
+    if ((bits_qk != 8 && bits_qk != 4 && bits_qk != 16) || (bits_pv != 8 && bits_pv != 4 && bits_pv != 16))
+        return fail(PARO_EINVAL, "bits (qk=%d, pv=%d): expected 4, 8 or 16", bits_qk, bits_pv);
+    const int64_t total = (int64_t)s->B * s->nh * k;
+    const int64_t per_xcd = (total + 7) / 8;  // the kernels give launch positions [x*per_xcd, (x+1)*per_xcd) to XCD x
+    // Heads whose K and V operands fit one XCD's L2 together are scheduled as one group, so that
+    // starting the heaviest rows first never costs the L2 residency of K/V.
+    const int64_t kv_bytes = k * s->block * (int64_t)s->d * (bits_qk + bits_pv) / 8;
+    const int64_t l2_budget = 3 << 20;
+    const int64_t window = std::max<int64_t>(1, l2_budget / std::max<int64_t>(kv_bytes, 1));
+    std::vector<int32_t> ids;
+    for (int x = 0; x < 8; ++x) {
+        const int64_t lo = x * per_xcd, hi = std::min(total, (x + 1) * per_xcd);
+        int64_t pos = lo;
+        while (pos < hi) {
+            const int64_t group = (pos / k) / window;
+            int64_t end = pos;
+            while (end < hi && (end / k) / window == group) ++end;
+            ids.resize(end - pos);
+            for (int64_t t = pos; t < end; ++t) ids[t - pos] = (int32_t)t;
+            auto live = [&](int32_t id) {
+                const int64_t h = (id / k) % s->nh, i = id % k;
+                return h_row_ptr[h * (k + 1) + i + 1] - h_row_ptr[h * (k + 1) + i];
+            };
+            std::stable_sort(ids.begin(), ids.end(), [&](int32_t a, int32_t b) { return live(a) > live(b); });
+            for (int64_t t = pos; t < end; ++t) h_order[t] = ids[t - pos];
+            pos = end;
+        }
+    }
     return PARO_OK;
 }
 

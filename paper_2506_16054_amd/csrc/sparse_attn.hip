@@ -53,6 +53,7 @@ struct AttnArgs {
     int n_tokens;
     int total_wg;  // B * nh * kblocks
     int per_xcd;   // ceil(total_wg / 8)
+    const int* row_order;  // optional [total_wg]: (b*nh + h)*k + i of the row block that runs at each launch position
     float qk_scale;  // log2(e) / sqrt(d)
     int scatter;     // 1: store row n' of the result at row idx(n') of o [B,nh,N,d] (Sec. 4.1 inverse reorder
                      //    done by adjusting the write-back address); 0: store op [B,nh,Npad,d]
@@ -143,8 +144,9 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     const int wg = blockIdx.x;
     const int logical = (wg & 7) * a.per_xcd + (wg >> 3);
     if (logical >= a.total_wg) return;
-    const int bh = logical / a.kblocks;
-    const int i = logical - bh * a.kblocks;
+    const int item = a.row_order ? min(max(a.row_order[logical], 0), a.total_wg - 1) : logical;
+    const int bh = item / a.kblocks;
+    const int i = item - bh * a.kblocks;
     const int h = bh % a.nh;
 
     const int tid = threadIdx.x;
@@ -434,8 +436,9 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
     const int wg = blockIdx.x;
     const int logical = (wg & 7) * a.per_xcd + (wg >> 3);
     if (logical >= a.total_wg) return;
-    const int bh = logical / a.kblocks;
-    const int i = logical - bh * a.kblocks;
+    const int item = a.row_order ? min(max(a.row_order[logical], 0), a.total_wg - 1) : logical;
+    const int bh = item / a.kblocks;
+    const int i = item - bh * a.kblocks;
     const int h = bh % a.nh;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -649,7 +652,8 @@ static void launch_i8(int blk, int d, paro_dtype out_dtype, const AttnArgs& a, h
 namespace paro {
 static int attn_entry(const char* what, const paro_shape* s, int bits_qk, int bits_pv, const void* q, const float* sq, const void* k,
                       const float* sk, const void* v, const float* sv, const int32_t* row_ptr, const int32_t* col_idx,
-                      int64_t nnz, const uint8_t* h_perm_ids, paro_dtype out_dtype, void* op, void* stream) {
+                      int64_t nnz, const int32_t* row_order, const uint8_t* h_perm_ids, paro_dtype out_dtype, void* op,
+                      void* stream) {
     int64_t n, kb;
     if (int st = check_shape(s, &n, &kb)) return st;
     const bool i8 = bits_qk == 8 && (bits_pv == 8 || bits_pv == 4);
@@ -681,6 +685,7 @@ static int attn_entry(const char* what, const paro_shape* s, int bits_qk, int bi
     a.n_tokens = (int)n;
     a.total_wg = (int)((int64_t)s->B * s->nh * kb);
     a.per_xcd = (a.total_wg + 7) / 8;
+    a.row_order = row_order;
     a.qk_scale = (float)(1.4426950408889634 / sqrt((double)s->d));
     a.scatter = h_perm_ids != nullptr;
     if (a.scatter) {
@@ -703,16 +708,18 @@ static int attn_entry(const char* what, const paro_shape* s, int bits_qk, int bi
 
 extern "C" int paro_sparse_attn(const paro_shape* s, int bits_qk, int bits_pv, const void* q, const float* sq, const void* k,
                                 const float* sk, const void* v, const float* sv, const int32_t* row_ptr,
-                                const int32_t* col_idx, int64_t nnz, paro_dtype out_dtype, void* op, void* stream) {
-    return paro::attn_entry("paro_sparse_attn", s, bits_qk, bits_pv, q, sq, k, sk, v, sv, row_ptr, col_idx, nnz, nullptr, out_dtype,
-                            op, stream);
+                                const int32_t* col_idx, int64_t nnz, const int32_t* row_order, paro_dtype out_dtype, void* op,
+                                void* stream) {
+    return paro::attn_entry("paro_sparse_attn", s, bits_qk, bits_pv, q, sq, k, sk, v, sv, row_ptr, col_idx, nnz, row_order, nullptr,
+                            out_dtype, op, stream);
 }
 
 extern "C" int paro_sparse_attn_unpermuted(const paro_shape* s, int bits_qk, int bits_pv, const void* q, const float* sq,
                                            const void* k, const float* sk, const void* v, const float* sv,
                                            const int32_t* row_ptr, const int32_t* col_idx, int64_t nnz,
-                                           const uint8_t* h_perm_ids, paro_dtype out_dtype, void* o, void* stream) {
+                                           const int32_t* row_order, const uint8_t* h_perm_ids, paro_dtype out_dtype,
+                                           void* o, void* stream) {
     if (!h_perm_ids) return paro::fail(PARO_EINVAL, "perm_ids is NULL");
     return paro::attn_entry("paro_sparse_attn_unpermuted", s, bits_qk, bits_pv, q, sq, k, sk, v, sv, row_ptr, col_idx, nnz,
-                            h_perm_ids, out_dtype, o, stream);
+                            row_order, h_perm_ids, out_dtype, o, stream);
 }

@@ -25,6 +25,8 @@ class ParoAttention:
         self.row_ptr = torch.from_numpy(row_ptr).to(self.dev)
         self.col_idx = torch.from_numpy(col_idx).to(self.dev)
         self.live_blocks = int(col_idx.size) * shape.B
+        self.h_row_order = pb.paro_schedule_rows(shape, bits_qk, bits_pv, row_ptr)
+        self.row_order = torch.from_numpy(self.h_row_order).to(self.dev)
         B, nh, d = shape.B, shape.nh, shape.d
         ct_qk = torch.bfloat16 if bits_qk == 16 else torch.int8
         ct_pv = torch.bfloat16 if bits_pv == 16 else torch.int8
@@ -51,7 +53,7 @@ class ParoAttention:
 
     def attend(self) -> None:
         pb.paro_sparse_attn(self.s, self.bits_qk, self.bits_pv, self.qc, self.sq, self.kc, self.sk, self.vc, self.sv,
-                            self.row_ptr, self.col_idx, self.op)
+                            self.row_ptr, self.col_idx, self.op, self.row_order)
 
     def finish(self):
         pb.paro_unpermute(self.s, self.perm_ids, self.op, self.o)
@@ -83,7 +85,7 @@ class ParoAttention:
     def attend_fused(self):
         fq, fk = self._fused_buffers()
         pb.paro_sparse_attn_unpermuted(self.s, self.bits_qk, self.bits_pv, fq, self.sq, fk, self.sk, self.vc, self.sv,
-                                       self.row_ptr, self.col_idx, self.perm_ids, self.o)
+                                       self.row_ptr, self.col_idx, self.perm_ids, self.o, self.row_order)
         return self.o
 
     def run_fused(self, q, k, v):

@@ -286,3 +286,18 @@ def test_fused_entry_points_are_bit_identical_to_the_separate_steps(name):
         for got, ref in zip((pa.sq, pa.sk, pa.sv), ref_s):
             assert torch.equal(got, ref)
     assert torch.equal(o, ref_o)
+
+
+@pytest.mark.parametrize("name", ["video64", "flux128", "video64_bf16"])
+def test_row_schedule_does_not_change_results(name):
+    torch, pb = _torch(), _pb()
+    p = problem(name)
+    pa = p.pa
+    pa.attend()  # scheduled order (the pipeline's default)
+    torch.cuda.synchronize()
+    ref = pa.op.clone()
+    pa.op.fill_(float("nan"))
+    pb.paro_sparse_attn(pa.s, pa.bits_qk, pa.bits_pv, pa.qc, pa.sq, pa.kc, pa.sk, pa.vc, pa.sv, pa.row_ptr, pa.col_idx, pa.op, None)
+    torch.cuda.synchronize()
+    assert torch.equal(pa.op, ref)
+    assert not np.array_equal(pa.h_row_order, np.arange(pa.h_row_order.size))

@@ -111,8 +111,58 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
     assert L.paro_quantize(ctypes.byref(s), pb.PARO_F32, 8, 3, fake, ctypes.c_void_p(0x2000), fake, None) == pb.PARO_EINVAL
     assert L.paro_quantize(ctypes.byref(s), pb.PARO_F32, 8, pb.PARO_VT, fake, None, fake, None) == pb.PARO_EINVAL
     args = [fake, fake, fake, fake, fake, fake, fake, fake]
-    assert L.paro_sparse_attn(ctypes.byref(s), 4, 8, *args, 4, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
-    assert L.paro_sparse_attn(ctypes.byref(s), 8, 16, *args, 4, pb.PARO_F32, fake, None) == pb.PARO_EUNSUPPORTED
-    assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, *args, -1, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
-    assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, fake, None, fake, fake, fake, fake, fake, fake, 4, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
-    assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, *args, 4, 5, fake, None) == pb.PARO_EINVAL
+    assert L.paro_sparse_attn(ctypes.byref(s), 4, 8, *args, 4, None, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
+    assert L.paro_sparse_attn(ctypes.byref(s), 8, 16, *args, 4, None, pb.PARO_F32, fake, None) == pb.PARO_EUNSUPPORTED
+    assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, *args, -1, None, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
+    assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, fake, None, fake, fake, fake, fake, fake, fake, 4, None, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
+    assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, *args, 4, None, 5, fake, None) == pb.PARO_EINVAL
+
+
+def test_fused_entry_points_validate_on_the_host():
+    L = pb.lib()
+    s = pb.make_shape(1, 2, 64, 2, 8, 8, 0, 32)
+    fake = ctypes.c_void_p(0x1000)
+    ok = np.array([0, 5], np.uint8)
+    bad = np.array([0, 7], np.uint8)
+    assert L.paro_permute_quantize(ctypes.byref(s), pb.PARO_F32, 8, pb.PARO_ROWS, None, fake, ctypes.c_void_p(0x2000), fake, None) == pb.PARO_EINVAL
+    assert L.paro_permute_quantize(ctypes.byref(s), pb.PARO_F32, 8, pb.PARO_ROWS, bad.ctypes.data, fake, ctypes.c_void_p(0x2000), fake, None) == pb.PARO_EINVAL
+    assert L.paro_permute_quantize(ctypes.byref(s), pb.PARO_F32, 3, pb.PARO_ROWS, ok.ctypes.data, fake, ctypes.c_void_p(0x2000), fake, None) == pb.PARO_EINVAL
+    args = [fake] * 8
+    assert L.paro_sparse_attn_unpermuted(ctypes.byref(s), 8, 8, *args, 4, None, None, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
+    assert L.paro_sparse_attn_unpermuted(ctypes.byref(s), 8, 8, *args, 4, None, bad.ctypes.data, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
+
+
+def test_row_schedule_is_a_permutation_heaviest_first_within_l2_groups():
+    rng = np.random.default_rng(5)
+    # headline shape: one head's K+V (2.25 MB) fills the L2 budget alone -> groups of one head
+    s = pb.make_shape(1, 48, 64, 13, 30, 45, 0, 64)
+    k = 275
+    live = rng.integers(1, 120, size=(48, k))
+    rp = np.zeros((48, k + 1), np.int32)
+    rp[:, 1:] = np.cumsum(live, axis=1)
+    rp += np.concatenate([[0], np.cumsum(live.sum(1))[:-1]])[:, None].astype(np.int32)
+    order = pb.paro_schedule_rows(s, 8, 8, rp)
+    total = 48 * k
+    assert order.dtype == np.int32 and np.array_equal(np.sort(order), np.arange(total))
+    per_xcd = (total + 7) // 8
+    for x in range(8):
+        chunk = order[x * per_xcd:(x + 1) * per_xcd]
+        assert np.array_equal(np.sort(chunk), np.arange(x * per_xcd, min(total, (x + 1) * per_xcd)))  # XCD ranges are kept
+        heads = chunk // k
+        assert np.all(np.diff(heads) >= 0)  # heads stay in order: one head per L2 group
+        for h in np.unique(heads):
+            lv = live[h, chunk[heads == h] % k]
+            assert np.all(np.diff(lv) <= 0)  # heaviest first
+    # Flux shape: 1.18 MB per head -> two heads per group, sorted together
+    s2 = pb.make_shape(1, 24, 128, 1, 64, 64, 512, 64)
+    k2 = 72
+    live2 = rng.integers(1, 73, size=(24, k2))
+    rp2 = np.zeros((24, k2 + 1), np.int32)
+    rp2[:, 1:] = np.cumsum(live2, axis=1)
+    order2 = pb.paro_schedule_rows(s2, 8, 8, rp2)
+    assert np.array_equal(np.sort(order2), np.arange(24 * k2))
+    first_group = order2[: 2 * k2]
+    assert set(first_group // k2) == {0, 1}
+    assert np.all(np.diff(live2[first_group // k2, first_group % k2]) <= 0)
+    with pytest.raises(pb.ParoError):
+        pb.paro_schedule_rows(s2, 5, 8, rp2)
