@@ -466,8 +466,18 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
         for (int s = 0; s < KS; ++s) qf[s] = *(const v8bf*)(qrow + 32 * s);
     }
 
+    // column indices: 64 per fetch, one per lane, read back with v_readlane (as in the INT8 kernel)
+    auto load_cols = [&](int chunk) {
+        const int idx = min(chunk * 64 + lane, cnt - 1);
+        return cnt > 0 && chunk * 64 < cnt ? min(max(cols[idx], 0), a.kblocks - 1) : 0;
+    };
+    int cols_cur = load_cols(0), cols_nxt = load_cols(1);
+    int cur_chunk = 0;
+    auto col_of = [&](int t) {
+        return (t >> 6) == cur_chunk ? __builtin_amdgcn_readlane(cols_cur, t & 63) : __builtin_amdgcn_readlane(cols_nxt, t & 63);
+    };
+
     v4i kreg[NKC], vreg[NVC];
-    auto col_of = [&](int t) { return min(max(cols[t], 0), a.kblocks - 1); };
     auto gload = [&](int t) {
         const int j = col_of(t);
         const uint8_t* kp = kbase + (size_t)j * (BLK * D * 2);
@@ -530,7 +540,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
             }
         }
         if constexpr (TAIL) {
-            const int nkeys = a.n_tokens - col_of(t) * BLK;
+            const int nkeys = a.n_tokens - (a.kblocks - 1) * BLK;
 #pragma unroll
             for (int T = 0; T < KT; ++T)
 #pragma unroll
@@ -550,6 +560,11 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
         const float m_new = fmaxf(m, c * mx);
         __syncthreads();
         if (t + 1 < cnt) lstore_v(next);
+        if (((t + 2) & 63) == 0) {
+            cols_cur = cols_nxt;
+            ++cur_chunk;
+            cols_nxt = load_cols(cur_chunk + 1);
+        }
         if (t + 2 < cnt) gload(t + 2);
         const float alpha = __builtin_amdgcn_exp2f(m - m_new);
         m = m_new;
@@ -590,7 +605,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
         stage = next;
     };
 
-    const bool has_tail = (a.n_tokens % BLK) != 0 && cnt > 0 && col_of(cnt - 1) == a.kblocks - 1;
+    const bool has_tail = (a.n_tokens % BLK) != 0 && cnt > 0 && min(max(cols[cnt - 1], 0), a.kblocks - 1) == a.kblocks - 1;
     const int cnt_main = has_tail ? cnt - 1 : cnt;
     for (int t = 0; t < cnt_main; ++t) step(std::false_type{}, t);
     if (has_tail) step(std::true_type{}, cnt - 1);
