@@ -47,6 +47,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=50,
                     help="untimed steps; the GPU clock takes some tens of milliseconds of load to settle")
     ap.add_argument("--workload", default="cogvideox5b")
+    ap.add_argument("--density", type=float, default=None, help="override the workload's mask density (density sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target wall time of the oracle sample")
     return ap.parse_args()
@@ -136,6 +137,8 @@ def main():
     from paper_2506_16054_amd.pipeline import ParoAttention
 
     w = wl.WORKLOADS[args.workload]
+    if args.density is not None:
+        w = w.replace(density=args.density)
     s = pb.shape_of(w)
 
     # ---- static per-head data (host): axis orders, block masks, block list
