@@ -148,9 +148,10 @@ int paro_quantize(const paro_shape* s, paro_dtype dtype, int bits, paro_layout l
  *     sP  = max(Pt over the block x block tile, rows < N) / qmax_P;  Pc = round_half_even(Pt / sP)
  *     acc = acc*exp(m-m') + sP * sv[j] * (Pc Vc_j)       integer product, i32 accumulate
  * and finally op_i = acc / l (zeros if the row block has no live block).
- *   bits_qk  8 (int8 codes, PARO_ROWS) or 16 (bf16 values from paro_quantize(bits 16), PARO_ROWS)
+ *   bits_qk  8 or 4 (codes, PARO_ROWS; 4-bit codes are widened to 8 bits on chip, gfx950 has no
+ *            4-bit matrix instruction) or 16 (bf16 values from paro_quantize(bits 16), PARO_ROWS)
  *   bits_pv  8 or 4 (codes, PARO_VT, P quantized to the same width) or 16 (bf16, PARO_VT, P kept
- *            in bf16);  supported pairs: (8,8), (8,4), (16,16)
+ *            in bf16);  supported pairs: qk in {8,4} with pv in {8,4}, and (16,16)
  *   q,k      [B,nh,Npad,d] as produced by paro_quantize(..., PARO_ROWS, ...)
  *   v        as produced by paro_quantize(..., PARO_VT, ...)
  *   sq,sk,sv float32 [B,nh,k] (ignored, may be NULL, when the operand is 16-bit)

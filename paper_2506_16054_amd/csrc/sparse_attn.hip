@@ -117,7 +117,18 @@ __device__ inline float int_result(int raw) { return __int_as_float(raw) - kAccB
 #define PARO_ATTN_WAVES_D64 3  // wavefronts per SIMD the register allocation must allow, d = 64
 #endif
 
-template <int BLK, int D, int PVBITS, typename OutT>
+// 16 bytes of packed 4-bit codes -> 32 signed bytes holding the codes times 16: a nibble moved to
+// the top of its byte is the two's-complement code scaled by 16; the factor is undone in the
+// scale.  Of every 8 codes the four even ones come first, then the four odd ones - a fixed
+// permutation of the contraction index that Q and K (or P and V) share.
+__device__ inline void unpack_nibbles(const v4i x, v4i& first, v4i& second) {
+    const v4i lo = (x << 4) & (int)0xF0F0F0F0;
+    const v4i hi = x & (int)0xF0F0F0F0;
+    first = v4i{lo.x, hi.x, lo.y, hi.y};
+    second = v4i{lo.z, hi.z, lo.w, hi.w};
+}
+
+template <int BLK, int D, int QKBITS, int PVBITS, typename OutT>
 __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void attn_i8_kernel(AttnArgs a) {
     constexpr int NW = BLK / 32;
     constexpr int NT = 64 * NW;
@@ -127,7 +138,8 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     constexpr int VBYTES = D * VSTR;
     constexpr int STAGE = KBYTES + VBYTES;
     constexpr int VPACK = PVBITS == 4 ? 2 : 1;
-    constexpr int NKC = BLK * D / 16 / NT;          // 16-byte pieces of a K tile per thread
+    constexpr int KPACK = QKBITS == 4 ? 2 : 1;
+    constexpr int NKC = BLK * D / KPACK / 16 / NT;  // 16-byte pieces of a K tile per thread
     constexpr int NVC = BLK * D / VPACK / 16 / NT;  // 16-byte pieces of a V tile per thread
     constexpr int KS = D / 32;    // contraction steps of QK^T
     constexpr int KT = BLK / 32;  // 32-key tiles per block
@@ -164,14 +176,23 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     const size_t head_rows = (size_t)bh * a.kblocks * BLK;
     const int row = i * BLK + 32 * w + n;  // this lane's query, in the reordered sequence
     const bool row_valid = row < a.n_tokens;
-    const uint8_t* kbase = a.k + head_rows * D;
+    const uint8_t* kbase = a.k + head_rows * D / KPACK;
     const uint8_t* vbase = a.v + head_rows * D / VPACK;
     const float* skp = a.sk + (size_t)bh * a.kblocks;
     const float* svp = a.sv + (size_t)bh * a.kblocks;
-    const float sq_i = a.sq[(size_t)bh * a.kblocks + i] * a.qk_scale;
+    // 4-bit Q and K codes both enter the product times 16
+    const float sq_i = a.sq[(size_t)bh * a.kblocks + i] * a.qk_scale * (QKBITS == 4 ? 1.0f / 256.0f : 1.0f);
 
     v4i qf[KS];
-    {
+    if constexpr (QKBITS == 4) {
+        const uint8_t* qrow = a.q + ((head_rows + row) * D + 16 * g) / 2;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const uint2 x = *(const uint2*)(qrow + 16 * s);  // 16 codes of this lane's contraction slice
+            v4i unused;
+            unpack_nibbles(v4i{(int)x.x, (int)x.y, 0, 0}, qf[s], unused);
+        }
+    } else {
         const uint8_t* qrow = a.q + (head_rows + row) * D + 16 * g;
 #pragma unroll
         for (int s = 0; s < KS; ++s) qf[s] = *(const v4i*)(qrow + 32 * s);
@@ -193,7 +214,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     float sk_reg = 0.0f, sv_reg = 0.0f;  // scales of the block whose tiles sit in kreg / vreg
     auto gload = [&](int t) {
         const int j = col_of(t);
-        const uint8_t* kp = kbase + (size_t)j * (BLK * D);
+        const uint8_t* kp = kbase + (size_t)j * (BLK * D / KPACK);
         const uint8_t* vp = vbase + (size_t)j * (BLK * D / VPACK);
         sk_reg = skp[j];
         sv_reg = svp[j];
@@ -207,7 +228,16 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 #pragma unroll
         for (int c = 0; c < NKC; ++c) {
             const int o = 16 * (tid + NT * c);
-            *(v4i*)(ks + (o / D) * KSTR + (o % D)) = kreg[c];
+            if constexpr (QKBITS == 4) {  // 16 packed bytes = 32 channels of one key
+                constexpr int PROW = D / 2;
+                v4i first, second;
+                unpack_nibbles(kreg[c], first, second);
+                uint8_t* dst = ks + (o / PROW) * KSTR + 2 * (o % PROW);
+                *(v4i*)dst = first;
+                *(v4i*)(dst + 16) = second;
+            } else {
+                *(v4i*)(ks + (o / D) * KSTR + (o % D)) = kreg[c];
+            }
         }
     };
     auto lstore_v = [&](int stage) {
@@ -216,15 +246,14 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
         for (int c = 0; c < NVC; ++c) {
             const int o = 16 * (tid + NT * c);
             if constexpr (PVBITS == 4) {
-                // 16 packed bytes = 32 slots of one channel.  A nibble moved to the top of its
-                // byte is the code times 16 as a signed byte; the factor is undone in the scale.
+                // 16 packed bytes = 32 slots of one channel (the PARO_VT nibble order makes the
+                // unpacked bytes land in slot order)
                 constexpr int PROW = BLK / 2;
-                const v4i x = vreg[c];
-                const v4i lo = (x << 4) & (int)0xF0F0F0F0;
-                const v4i hi = x & (int)0xF0F0F0F0;
+                v4i first, second;
+                unpack_nibbles(vreg[c], first, second);
                 uint8_t* dst = vs + (o / PROW) * VSTR + 2 * (o % PROW);
-                *(v4i*)dst = v4i{lo.x, hi.x, lo.y, hi.y};
-                *(v4i*)(dst + 16) = v4i{lo.z, hi.z, lo.w, hi.w};
+                *(v4i*)dst = first;
+                *(v4i*)(dst + 16) = second;
             } else {
                 *(v4i*)(vs + (o / BLK) * VSTR + (o % BLK)) = vreg[c];
             }
@@ -645,21 +674,21 @@ static int launch_bf16(int blk, int d, const AttnArgs& a, hipStream_t st) {
     return launch_bf16_t<32, 128, OutT>(a, st);
 }
 
-template <int BLK, int D, int PVBITS>
+template <int BLK, int D, int QKBITS, int PVBITS>
 static void launch_out(paro_dtype out_dtype, const AttnArgs& a, hipStream_t st) {
     dim3 grid((unsigned)(a.per_xcd * 8));
     if (out_dtype == PARO_F32)
-        hipLaunchKernelGGL((attn_i8_kernel<BLK, D, PVBITS, float>), grid, dim3(BLK * 2), 0, st, a);
+        hipLaunchKernelGGL((attn_i8_kernel<BLK, D, QKBITS, PVBITS, float>), grid, dim3(BLK * 2), 0, st, a);
     else
-        hipLaunchKernelGGL((attn_i8_kernel<BLK, D, PVBITS, uint16_t>), grid, dim3(BLK * 2), 0, st, a);
+        hipLaunchKernelGGL((attn_i8_kernel<BLK, D, QKBITS, PVBITS, uint16_t>), grid, dim3(BLK * 2), 0, st, a);
 }
 
-template <int PVBITS>
+template <int QKBITS, int PVBITS>
 static void launch_i8(int blk, int d, paro_dtype out_dtype, const AttnArgs& a, hipStream_t st) {
-    if (blk == 64 && d == 64) launch_out<64, 64, PVBITS>(out_dtype, a, st);
-    else if (blk == 64 && d == 128) launch_out<64, 128, PVBITS>(out_dtype, a, st);
-    else if (blk == 32 && d == 64) launch_out<32, 64, PVBITS>(out_dtype, a, st);
-    else launch_out<32, 128, PVBITS>(out_dtype, a, st);
+    if (blk == 64 && d == 64) launch_out<64, 64, QKBITS, PVBITS>(out_dtype, a, st);
+    else if (blk == 64 && d == 128) launch_out<64, 128, QKBITS, PVBITS>(out_dtype, a, st);
+    else if (blk == 32 && d == 64) launch_out<32, 64, QKBITS, PVBITS>(out_dtype, a, st);
+    else launch_out<32, 128, QKBITS, PVBITS>(out_dtype, a, st);
 }
 
 }  // namespace paro
@@ -671,11 +700,12 @@ static int attn_entry(const char* what, const paro_shape* s, int bits_qk, int bi
                       void* stream) {
     int64_t n, kb;
     if (int st = check_shape(s, &n, &kb)) return st;
-    const bool i8 = bits_qk == 8 && (bits_pv == 8 || bits_pv == 4);
+    const bool i8 = (bits_qk == 8 || bits_qk == 4) && (bits_pv == 8 || bits_pv == 4);
     const bool b16 = bits_qk == 16 && bits_pv == 16;
     if (!i8 && !b16) {
-        const bool known = (bits_qk == 8 || bits_qk == 16) && (bits_pv == 8 || bits_pv == 4 || bits_pv == 16);
-        return fail(known ? PARO_EUNSUPPORTED : PARO_EINVAL, "bits (qk=%d, pv=%d): supported pairs are (8,8), (8,4), (16,16)", bits_qk, bits_pv);
+        const bool known = (bits_qk == 8 || bits_qk == 4 || bits_qk == 16) && (bits_pv == 8 || bits_pv == 4 || bits_pv == 16);
+        return fail(known ? PARO_EUNSUPPORTED : PARO_EINVAL,
+                    "bits (qk=%d, pv=%d): supported pairs are qk in {8,4} with pv in {8,4}, and (16,16)", bits_qk, bits_pv);
     }
     if (out_dtype != PARO_F32 && out_dtype != PARO_BF16) return fail(PARO_EINVAL, "out_dtype=%d is not a paro_dtype", (int)out_dtype);
     if (!q || !k || !v || !op || !row_ptr) return fail(PARO_EINVAL, "q, k, v, op and row_ptr must not be NULL");
@@ -712,10 +742,12 @@ static int attn_entry(const char* what, const paro_shape* s, int bits_qk, int bi
         const int st = out_dtype == PARO_F32 ? launch_bf16<float>(s->block, s->d, a, (hipStream_t)stream)
                                              : launch_bf16<uint16_t>(s->block, s->d, a, (hipStream_t)stream);
         if (st) return st;
-    } else if (bits_pv == 8) {
-        launch_i8<8>(s->block, s->d, out_dtype, a, (hipStream_t)stream);
+    } else if (bits_qk == 8) {
+        if (bits_pv == 8) launch_i8<8, 8>(s->block, s->d, out_dtype, a, (hipStream_t)stream);
+        else launch_i8<8, 4>(s->block, s->d, out_dtype, a, (hipStream_t)stream);
     } else {
-        launch_i8<4>(s->block, s->d, out_dtype, a, (hipStream_t)stream);
+        if (bits_pv == 8) launch_i8<4, 8>(s->block, s->d, out_dtype, a, (hipStream_t)stream);
+        else launch_i8<4, 4>(s->block, s->d, out_dtype, a, (hipStream_t)stream);
     }
     return check_launch(what);
 }

@@ -11,7 +11,7 @@ import pytest
 from oracle import paro_oracle as po
 from paper_2506_16054_amd import workloads as wl
 from tests.helpers import KERNEL_TIE_TOL, check_attention
-from tests.test_gpu_parity import MAX_ABS, REL_L2, REL_L2_BF16, host, tdtype, unpack_vt_int4, vt_to_rows
+from tests.test_gpu_parity import MAX_ABS, REL_L2, REL_L2_BF16, host, tdtype, unpack_rows_int4, unpack_vt_int4, vt_to_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -63,9 +63,12 @@ def check_sampled(w, heads):
         qc, sq = po.prepare_operand(hq, idx, w.npad, w.block, w.bits_qk)
         kc, sk = po.prepare_operand(hk, idx, w.npad, w.block, w.bits_qk)
         vc, sv = po.prepare_operand(hv, idx, w.npad, w.block, w.bits_pv)
-        if w.bits_qk == 8:
-            assert np.array_equal(pa.qc[0, h].cpu().numpy().astype(np.int32), qc)
-            assert np.array_equal(pa.kc[0, h].cpu().numpy().astype(np.int32), kc)
+        if w.bits_qk != 16:
+            g_q, g_k = pa.qc[0, h].cpu().numpy(), pa.kc[0, h].cpu().numpy()
+            if w.bits_qk == 4:
+                g_q, g_k = unpack_rows_int4(g_q), unpack_rows_int4(g_k)
+            assert np.array_equal(g_q.astype(np.int32), qc)
+            assert np.array_equal(g_k.astype(np.int32), kc)
             g_vc = pa.vc[0, h].cpu().numpy()
             g_vc = unpack_vt_int4(g_vc) if w.bits_pv == 4 else g_vc.astype(np.int32)
             assert np.array_equal(vt_to_rows(g_vc, w.block), vc)
@@ -108,3 +111,7 @@ def test_flux_text_blocks_d128():
 
 def test_headline_shape_bf16_mode():
     check_sampled(wl.WORKLOADS["cogvideox5b"].replace(name="cogvideox5b_bf16", bits_qk=16, bits_pv=16, nh=8), heads=(2, 7))
+
+
+def test_headline_shape_all_int4():
+    check_sampled(wl.WORKLOADS["cogvideox5b"].replace(name="cogvideox5b_i4i4", bits_qk=4, bits_pv=4, density=0.5, nh=8), heads=(1, 6))

@@ -84,6 +84,10 @@ SMALL = {
     "video32_bf16_f32io": wl.Workload("video32_bf16_f32io", 1, 2, 64, 3, 7, 9, 0, 32, 0.5, 16, 16, "f32", 18, perm_choice=(2, 4)),
     "flux128_b32_bf16": wl.Workload("flux128_b32_bf16", 1, 1, 128, 1, 8, 12, 32, 32, 0.5, 16, 16, "bf16", 19, perm_choice=(5,)),
 }
+# INT4 QK^T (the paper's all-INT4 setting) and the mixed INT4 QK / INT8 PV
+SMALL["video64_i4i4"] = wl.Workload("video64_i4i4", 1, 2, 64, 5, 12, 13, 0, 64, 0.4, 4, 4, "bf16", 20, perm_choice=(3, 0))
+SMALL["flux128_i4i8_f32"] = wl.Workload("flux128_i4i8_f32", 1, 2, 128, 1, 16, 16, 64, 64, 0.3, 4, 8, "f32", 21, perm_choice=(0, 5))
+SMALL["video32_i4i4_f32"] = wl.Workload("video32_i4i4_f32", 1, 2, 64, 3, 7, 9, 0, 32, 0.5, 4, 4, "f32", 22, perm_choice=(2, 5))
 REL_L2_BF16 = 5e-3  # stated bar of the unquantized mode
 
 
@@ -161,8 +165,10 @@ def test_quantize_codes_and_scales_bit_exact(name):
     for b in range(w.B):
         for h in range(w.nh):
             r = p.oracle[b][h]
-            assert np.array_equal(qc[b, h].astype(np.int32), r["qc"])
-            assert np.array_equal(kc[b, h].astype(np.int32), r["kc"])
+            g_q = unpack_rows_int4(qc[b, h]) if w.bits_qk == 4 else qc[b, h].astype(np.int32)
+            g_k = unpack_rows_int4(kc[b, h]) if w.bits_qk == 4 else kc[b, h].astype(np.int32)
+            assert np.array_equal(g_q, r["qc"])
+            assert np.array_equal(g_k, r["kc"])
             v_slots = unpack_vt_int4(vc[b, h]) if w.bits_pv == 4 else vc[b, h].astype(np.int32)
             assert np.array_equal(vt_to_rows(v_slots, w.block), r["vc"])
             assert np.array_equal(sq[b, h], r["sq"]) and np.array_equal(sk[b, h], r["sk"]) and np.array_equal(sv[b, h], r["sv"])
@@ -260,7 +266,8 @@ def test_empty_row_block_gives_zeros():
     check_attention(op, r["op"], r["flip_risk"], MAX_ABS, REL_L2)
 
 
-@pytest.mark.parametrize("name", ["video64", "video64_int4", "video32_f32", "flux128", "flux128_b32_int4", "video64_bf16", "video32_bf16_f32io"])
+@pytest.mark.parametrize("name", ["video64", "video64_int4", "video32_f32", "flux128", "flux128_b32_int4", "video64_bf16", "video32_bf16_f32io",
+                                  "video64_i4i4", "flux128_i4i8_f32"])
 def test_fused_entry_points_are_bit_identical_to_the_separate_steps(name):
     """paro_permute_quantize == paro_permute + paro_quantize and paro_sparse_attn_unpermuted ==
     paro_sparse_attn + paro_unpermute, bit for bit (so the oracle parity of the separate steps
@@ -282,7 +289,7 @@ def test_fused_entry_points_are_bit_identical_to_the_separate_steps(name):
     assert torch.equal(fq.view(torch.uint8) if fq.dtype == torch.int8 else fq, ref_q.view(torch.uint8) if ref_q.dtype == torch.int8 else ref_q)
     assert torch.equal(fk.view(torch.uint8) if fk.dtype == torch.int8 else fk, ref_k.view(torch.uint8) if ref_k.dtype == torch.int8 else ref_k)
     assert torch.equal(pa.vc, ref_v)
-    if p.w.bits_qk == 8:
+    if p.w.bits_qk != 16:
         for got, ref in zip((pa.sq, pa.sk, pa.sv), ref_s):
             assert torch.equal(got, ref)
     assert torch.equal(o, ref_o)

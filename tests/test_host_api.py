@@ -111,7 +111,7 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
     assert L.paro_quantize(ctypes.byref(s), pb.PARO_F32, 8, 3, fake, ctypes.c_void_p(0x2000), fake, None) == pb.PARO_EINVAL
     assert L.paro_quantize(ctypes.byref(s), pb.PARO_F32, 8, pb.PARO_VT, fake, None, fake, None) == pb.PARO_EINVAL
     args = [fake, fake, fake, fake, fake, fake, fake, fake]
-    assert L.paro_sparse_attn(ctypes.byref(s), 4, 8, *args, 4, None, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
+    assert L.paro_sparse_attn(ctypes.byref(s), 5, 8, *args, 4, None, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
     assert L.paro_sparse_attn(ctypes.byref(s), 8, 16, *args, 4, None, pb.PARO_F32, fake, None) == pb.PARO_EUNSUPPORTED
     assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, *args, -1, None, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
     assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, fake, None, fake, fake, fake, fake, fake, fake, 4, None, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
