@@ -202,9 +202,9 @@ def main():
     attn_ms = sorted(a.elapsed_time(b) for a, b in ev)
     attn_avg = sum(attn_ms) / len(attn_ms)
 
-    quantized = w.bits_qk == 8
+    quantized = w.bits_qk in (8, 4)
     # compulsory HBM bytes of one attention launch: Q, K, V operands read once, output written once
-    qk_bytes = 1 if quantized else 2
+    qk_bytes = {4: 0.5, 8: 1, 16: 2}[w.bits_qk]
     v_bytes = 0.5 if w.bits_pv == 4 else (1 if w.bits_pv == 8 else 2)
     algorithmic_bytes = int(w.B * w.nh * w.npad * w.d * (2 * qk_bytes + v_bytes) + w.B * w.nh * w.N * w.d * (2 if w.dtype == "bf16" else 4))
     peak = PEAK_INT8_TOPS if quantized else PEAK_BF16_TFLOPS
