@@ -11,6 +11,9 @@
  *                                   INT8 QK^T and INT8/INT4 PV with block-wise scales     Sec. 4.2 (2), 4.3
  *   paro_unpermute (O)              put output rows back into the default order          Sec. 4.1
  *
+ * plus fused forms of the reorder (Sec. 4.1) and the device-side mask expansion that the
+ * per-(transformer block, timestep) mask prefetch needs (Sec. 4.2 (1), App. C).
+ *
  * Conventions
  *   - Every function returns 0 (PARO_OK) or a negative paro_status.  Arguments are checked on
  *     the host before anything is launched; on error nothing has been enqueued and
@@ -190,6 +193,24 @@ int paro_sparse_attn_unpermuted(const paro_shape* s, int bits_qk, int bits_pv, c
                                 const float* sv, const int32_t* row_ptr, const int32_t* col_idx,
                                 int64_t nnz, const int32_t* row_order, const uint8_t* h_perm_ids,
                                 paro_dtype out_dtype, void* o, void* stream);
+
+/* ---- mask prefetch (Sec. 4.2 (1) "prefetching sparse masks"; App. C "Overhead of Prefetch") ----
+ * Masks differ per transformer block and timestep, so only the mask of the call at hand lives on
+ * the GPU: while attention runs with one block list, the caller copies the next bitmask to the
+ * device on a second stream and expands it there into a second block list (two buffers, used in
+ * turn).  This entry point is that expansion; it is paro_mask_to_blocklist with every pointer on
+ * the DEVICE, and produces the same row_ptr and col_idx, bit for bit.
+ *   bitmask  [nh][ceil(k*k/8)] bytes, layout as paro_mask_to_blocklist; bits at or above k*k of a
+ *            head are ignored
+ *   row_ptr  int32 [nh][k+1], written in full
+ *   col_idx  int32 [cap]; live blocks beyond `cap` entries are dropped (row_ptr still counts them:
+ *            pass the same cap as `nnz` to paro_sparse_attn, which clamps).  cap = nh*k*k always
+ *            suffices; cap may be 0 with col_idx NULL to obtain only row_ptr and the total.
+ *   nnz_out  optional int32 on the device: receives the number of live blocks
+ * The three small kernels it enqueues on `stream` read and write only these buffers; ordering
+ * against the attention call that consumes (or still reads) them is the caller's, by events. */
+int paro_mask_to_blocklist_device(int nh, int k, const uint8_t* bitmask, int32_t* row_ptr,
+                                  int32_t* col_idx, int64_t cap, int32_t* nnz_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -28,6 +28,7 @@ EXPORTS = (
     "paro_version", "paro_strerror", "paro_last_error", "paro_ntokens", "paro_nblocks", "paro_npad",
     "paro_perm_index", "paro_vt_slot", "paro_mask_to_blocklist", "paro_permute", "paro_unpermute",
     "paro_quantize", "paro_sparse_attn", "paro_permute_quantize", "paro_sparse_attn_unpermuted", "paro_schedule_rows",
+    "paro_mask_to_blocklist_device",
 )
 
 
@@ -70,6 +71,7 @@ def lib() -> ctypes.CDLL:
         L.paro_schedule_rows.argtypes = [sp, i32, i32, vp, vp]
         L.paro_permute_quantize.argtypes = [sp, i32, i32, i32, vp, vp, vp, vp, vp]
         L.paro_sparse_attn_unpermuted.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i32, vp, vp]
+        L.paro_mask_to_blocklist_device.argtypes = [i32, i32, vp, vp, vp, i64, vp, vp]
         _lib = L
     return _lib
 
@@ -238,6 +240,22 @@ def paro_permute_quantize(s: paro_shape, bits: int, layout: int, perm_ids, x, co
     p = _perm_bytes(s, perm_ids)
     _check(lib().paro_permute_quantize(ctypes.byref(s), _dtype_code(x), int(bits), int(layout), p.ctypes.data, _ptr(x), _ptr(codes),
                                        _ptr(scales), _stream()))
+
+
+def paro_mask_to_blocklist_device(nh: int, k: int, bitmask, row_ptr, col_idx, nnz_out=None) -> None:
+    """Device tensors: bitmask uint8 [nh, ceil(k*k/8)] -> row_ptr int32 [nh, k+1], col_idx int32 [cap]
+    (cap = col_idx.numel(); may be None for the offsets only), nnz_out int32 [1] or None."""
+    import torch
+
+    _require(bitmask, "bitmask", (nh, (k * k + 7) // 8), torch.uint8)
+    _require(row_ptr, "row_ptr", (nh, k + 1), torch.int32)
+    if col_idx is not None:
+        _require(col_idx, "col_idx", None, torch.int32)
+    if nnz_out is not None:
+        _require(nnz_out, "nnz_out", (1,), torch.int32)
+    cap = 0 if col_idx is None else int(col_idx.numel())
+    _check(lib().paro_mask_to_blocklist_device(int(nh), int(k), _ptr(bitmask), _ptr(row_ptr), _ptr(col_idx) if cap else None, cap,
+                                               _ptr(nnz_out), _stream()))
 
 
 def _attn_operands(s: paro_shape, bits_qk: int, bits_pv: int, q, sq, k, sk, v, sv, row_ptr, col_idx) -> None:

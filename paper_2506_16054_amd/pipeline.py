@@ -39,6 +39,11 @@ class ParoAttention:
         self.op = torch.empty((B, nh, self.npad, d), dtype=dtype, **z)
         self.o = torch.empty((B, nh, self.N, d), dtype=dtype, **z)
 
+    def use_blocklist(self, row_ptr, col_idx, row_order=None) -> None:
+        """Attend with another block list (device tensors), e.g. a slot of a MaskPrefetcher.  The
+        length of ``col_idx`` is passed to the kernels as the bound of the list."""
+        self.row_ptr, self.col_idx, self.row_order = row_ptr, col_idx, row_order
+
     def prepare(self, q, k, v) -> None:
         """paro_permute + paro_quantize for Q, K (row layout) and V (transposed-block layout)."""
         s = self.s
@@ -91,3 +96,74 @@ class ParoAttention:
     def run_fused(self, q, k, v):
         self.prepare_fused(q, k, v)
         return self.attend_fused()
+
+
+class MaskPrefetcher:
+    """Two device slots for the block list of the attention call at hand and of the next one
+    (paper Sec. 4.2 (1), App. C "Overhead of Prefetch").  All masks stay in pinned host memory as
+    bitmasks (with the launch order that belongs to each); ``prefetch(slot, t)`` copies mask ``t``
+    to slot ``slot`` on a second stream and expands it there with paro_mask_to_blocklist_device,
+    while the compute stream is busy with the other slot.  Ordering is by events only:
+
+        slot.ready   recorded on the copy stream after the expansion; the compute stream waits on
+                     it in ``acquire`` before the attention call that reads the slot;
+        slot.free    recorded on the compute stream in ``release`` after that attention call; the
+                     copy stream waits on it before it overwrites the slot.
+
+    Both streams have the default priority.  No arithmetic happens here."""
+
+    def __init__(self, shape: pb.paro_shape, h_bitmasks: np.ndarray, h_row_orders=None, cap=None, device="cuda:0"):
+        self.s = shape
+        self.dev = torch.device(device)
+        self.k = pb.paro_nblocks(shape)
+        nh, k = shape.nh, self.k
+        nbytes = (k * k + 7) // 8
+        bm = np.ascontiguousarray(h_bitmasks, dtype=np.uint8)
+        if bm.ndim != 3 or bm.shape[1:] != (nh, nbytes):
+            raise pb.ParoError(pb.PARO_EINVAL, "h_bitmasks has shape %s, expected (T, %d, %d)" % (bm.shape, nh, nbytes))
+        self.T = bm.shape[0]
+        self.h_bitmasks = torch.empty(bm.shape, dtype=torch.uint8, pin_memory=True)
+        self.h_bitmasks.copy_(torch.from_numpy(bm))
+        self.h_row_orders = None
+        if h_row_orders is not None:
+            ro = np.ascontiguousarray(h_row_orders, dtype=np.int32)
+            if ro.shape != (self.T, shape.B * nh * k):
+                raise pb.ParoError(pb.PARO_EINVAL, "h_row_orders has shape %s, expected (%d, %d)" % (ro.shape, self.T, shape.B * nh * k))
+            self.h_row_orders = torch.empty(ro.shape, dtype=torch.int32, pin_memory=True)
+            self.h_row_orders.copy_(torch.from_numpy(ro))
+        self.cap = int(cap) if cap is not None else nh * k * k
+        self.copy_stream = torch.cuda.Stream(self.dev)
+        z = dict(device=self.dev)
+        self.slots = []
+        for _ in range(2):
+            self.slots.append({
+                "bitmask": torch.empty((nh, nbytes), dtype=torch.uint8, **z),
+                "row_ptr": torch.zeros((nh, k + 1), dtype=torch.int32, **z),
+                "col_idx": torch.zeros((self.cap,), dtype=torch.int32, **z),
+                "row_order": None if self.h_row_orders is None else torch.empty((shape.B * nh * k,), dtype=torch.int32, **z),
+                "nnz": torch.zeros((1,), dtype=torch.int32, **z),
+                "ready": torch.cuda.Event(),
+                "free": torch.cuda.Event(),
+            })
+        torch.cuda.current_stream().synchronize()  # the slots exist before the copy stream touches them
+
+    def prefetch(self, slot: int, t: int) -> None:
+        """Enqueue, on the copy stream, the load and expansion of mask ``t`` into ``slot``."""
+        sl = self.slots[slot]
+        with torch.cuda.stream(self.copy_stream):
+            self.copy_stream.wait_event(sl["free"])
+            sl["bitmask"].copy_(self.h_bitmasks[t], non_blocking=True)
+            if sl["row_order"] is not None:
+                sl["row_order"].copy_(self.h_row_orders[t], non_blocking=True)
+            pb.paro_mask_to_blocklist_device(self.s.nh, self.k, sl["bitmask"], sl["row_ptr"], sl["col_idx"], sl["nnz"])
+            sl["ready"].record(self.copy_stream)
+
+    def acquire(self, slot: int):
+        """Make the current stream wait for the slot's block list; returns (row_ptr, col_idx, row_order)."""
+        sl = self.slots[slot]
+        torch.cuda.current_stream().wait_event(sl["ready"])
+        return sl["row_ptr"], sl["col_idx"], sl["row_order"]
+
+    def release(self, slot: int) -> None:
+        """Call after the attention launch that read the slot: the slot may be refilled once it is done."""
+        self.slots[slot]["free"].record(torch.cuda.current_stream())

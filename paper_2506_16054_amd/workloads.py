@@ -182,14 +182,16 @@ def block_locality_scores(w: Workload, gather_index: np.ndarray) -> np.ndarray:
     return np.add.reduceat(y, np.arange(0, n_img, blk), axis=0)
 
 
-def make_block_masks(w: Workload, gather_index_of: Callable[[int], np.ndarray], perm_ids=None) -> np.ndarray:
+def make_block_masks(w: Workload, gather_index_of: Callable[[int], np.ndarray], perm_ids=None,
+                     score_cache: Optional[Dict[int, np.ndarray]] = None) -> np.ndarray:
     """Per-head static block mask, bool [nh, k, k], defined on the reordered sequence.
 
     Stand-in for the paper's offline block-sum thresholding (Sec. 4.2 (3)): per head the
     diagonal is kept, then the image x image blocks with the highest locality score until
     ``rint(density * k_img^2)`` are live (one global threshold per head, so rows differ in
     live count).  Ties go to the lower (i, j).  Text rows and columns are always live
-    (Sec. 4.2 (1): sparsification applies to image tokens only).
+    (Sec. 4.2 (1): sparsification applies to image tokens only).  ``score_cache`` (order id ->
+    score map) may be shared between calls that differ only in density or seed.
     """
     if perm_ids is None:
         perm_ids = make_perm_ids(w)
@@ -198,7 +200,7 @@ def make_block_masks(w: Workload, gather_index_of: Callable[[int], np.ndarray], 
         raise ValueError("image tokens must fill whole blocks when text tokens follow")
     k_img = -(-w.n_img // blk)
     n_live = max(k_img, int(np.rint(w.density * k_img * k_img)))
-    cache: Dict[int, np.ndarray] = {}
+    cache: Dict[int, np.ndarray] = {} if score_cache is None else score_cache
     masks = np.zeros((w.nh, k, k), bool)
     for h in range(w.nh):
         pid = int(perm_ids[h])

@@ -116,6 +116,13 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
     assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, *args, -1, None, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
     assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, fake, None, fake, fake, fake, fake, fake, fake, 4, None, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
     assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, *args, 4, None, 5, fake, None) == pb.PARO_EINVAL
+    # device-side mask expansion
+    assert L.paro_mask_to_blocklist_device(0, 4, fake, fake, fake, 16, None, None) == pb.PARO_EINVAL
+    assert L.paro_mask_to_blocklist_device(2, 0, fake, fake, fake, 16, None, None) == pb.PARO_EINVAL
+    assert L.paro_mask_to_blocklist_device(2, 4, None, fake, fake, 16, None, None) == pb.PARO_EINVAL
+    assert L.paro_mask_to_blocklist_device(2, 4, fake, fake, None, 16, None, None) == pb.PARO_EINVAL
+    assert L.paro_mask_to_blocklist_device(2, 4, fake, fake, fake, -1, None, None) == pb.PARO_EINVAL
+    assert L.paro_mask_to_blocklist_device(200, 30000, fake, fake, fake, 16, None, None) == pb.PARO_EINVAL
 
 
 def test_fused_entry_points_validate_on_the_host():
