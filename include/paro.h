@@ -212,6 +212,62 @@ int paro_sparse_attn_unpermuted(const paro_shape* s, int bits_qk, int bits_pv, c
 int paro_mask_to_blocklist_device(int nh, int k, const uint8_t* bitmask, int32_t* row_ptr,
                                   int32_t* col_idx, int64_t cap, int32_t* nnz_out, void* stream);
 
+/* ---- offline calibration (Sec. 4.1 "Metric for Permutation Order"; Sec. 4.2 (3) "Efficient
+ * Offline Mask Generation") -----------------------------------------------------------------
+ * Run once per model on one or two calibration samples of Q and K: for each of the six axis
+ * orders, statistics of the b x b blocks of the post-softmax map P = softmax(Q K^T / sqrt(d)) of
+ * the reordered sequence give the two metrics of Sec. 4.1; the order with the lowest combined
+ * metric is chosen per head; block sums of the chosen order, thresholded at a requested density,
+ * give the head's static mask.  The map itself is never stored.
+ *
+ * Typical sequence, all on one stream:
+ *   for t in 0..5:  paro_permute_quantize(bits 16, PARO_ROWS, perm_ids = t for every head) on Q and K
+ *                   paro_calib_block_stats -> paro_calib_metrics(m_sparse6 + t*nh, m_quant6 + t*nh)
+ *   paro_calib_choose -> perm_ids (copy the nh bytes to the host: the other entry points take them there)
+ *   paro_permute_quantize(bits 16, chosen perm_ids) -> paro_calib_block_stats -> paro_calib_mask
+ *   -> bitmask, ready for paro_mask_to_blocklist(_device). */
+
+/* Per-block statistics of P for operands that are already reordered (Eq. (M_sparse), (M_quant)).
+ * P is formed from the 16-bit operands with fp32 accumulation; entries of padded rows and
+ * columns (beyond N) do not exist and enter no statistic.
+ *   q16, k16   bf16 [B,nh,Npad,d] as produced by paro_(permute_)quantize(bits 16, PARO_ROWS)
+ *   eps        threshold of Eq. (M_sparse) (paper: e.g. 1e-3), > 0
+ *   block_sum  float32 [B,nh,k,k]  sum of |P| over the block (the block sum of Sec. 4.2 (3))
+ *   block_max  float32 [B,nh,k,k]  max of |P| over the block
+ *   block_cnt  int32   [B,nh,k,k]  number of entries with |P| < eps  (n_ij of Eq. (M_sparse)) */
+int paro_calib_block_stats(const paro_shape* s, const void* q16, const void* k16, float eps,
+                           float* block_sum, float* block_max, int32_t* block_cnt, void* stream);
+
+/* The two metrics of one axis order per head (Eq. (M_sparse), Eq. (M_quant)), averaged over the B
+ * samples:  m_sparse[h] = share of blocks with n_ij >= sigma * entries_ij (compared in binary32;
+ * entries_ij = real entries of the block, b*b except in the ragged last row / column);
+ * m_quant[h] = mean over blocks of max|P_ij| / mean|P_ij| (0 for an all-zero block).
+ *   sigma in [0,1] (paper: e.g. 0.9);  m_sparse, m_quant: float32 [nh] */
+int paro_calib_metrics(const paro_shape* s, const float* block_sum, const float* block_max,
+                       const int32_t* block_cnt, float sigma, float* m_sparse, float* m_quant,
+                       void* stream);
+
+/* Combined metric (last equation of Sec. 4.1) and the chosen order per head.  The text defines
+ * M_sparse as the share of sparse blocks and picks the LOWEST combined value, so the sparsity
+ * term enters as the share of blocks that are not sparse, S = 1 - M_sparse:
+ *   M[t][h] = alpha * S[t][h] / sum_t S[t][h] + (1 - alpha) * Mq[t][h] / sum_t Mq[t][h]
+ * (a term whose normaliser is 0 is 0); perm_ids[h] = argmin_t M[t][h], lowest t on ties.
+ *   m_sparse6, m_quant6  float32 [6][nh], row t = paro_calib_metrics of axis order t
+ *   m_combined6          float32 [6][nh] (out);  perm_ids  uint8 [nh] (out, DEVICE) */
+int paro_calib_choose(int nh, const float* m_sparse6, const float* m_quant6, float alpha,
+                      float* m_combined6, uint8_t* perm_ids, void* stream);
+
+/* Static mask of every head by block-sum thresholding with density control (Sec. 4.2 (3)):
+ * among the k_img x k_img image blocks (k_img = ceil(F*Hg*Wg / block)) the
+ * n_live = round_half_even(density * k_img^2) blocks with the largest block sums (added over the
+ * B samples in sample order) are live; equal sums are taken in ascending i*k + j; rows and
+ * columns of text blocks are always live (Sec. 4.2 (1)).  Requires k*k <= 393216, and whole image
+ * blocks when text tokens follow.
+ *   block_sum  float32 [B,nh,k,k] from paro_calib_block_stats on the chosen order of each head
+ *   bitmask    uint8 [nh][ceil(k*k/8)] (out), layout as paro_mask_to_blocklist */
+int paro_calib_mask(const paro_shape* s, const float* block_sum, float density, uint8_t* bitmask,
+                    void* stream);
+
 #ifdef __cplusplus
 }
 #endif

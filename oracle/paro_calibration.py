@@ -104,6 +104,13 @@ def block_stats(p: np.ndarray, block: int, eps: float, tol: float = 0.0):
     return out
 
 
+def row_block_stats(q: np.ndarray, k: np.ndarray, idx: np.ndarray, i: int, block: int, eps: float, tol: float = 0.0):
+    """block_stats of row block ``i`` of the reordered map (all column blocks), without forming
+    the other rows: for sequences whose full map does not fit in memory."""
+    rows = idx[i * block:(i + 1) * block]
+    return block_stats(attention_rows(q, k, rows)[:, idx], block, eps, tol)
+
+
 def sparse_blocks(cnt: np.ndarray, entries: np.ndarray, sigma: float) -> np.ndarray:
     """Indicator of Eq. (M_sparse): n_ij / entries >= sigma, compared in binary32."""
     return cnt.astype(np.float32) >= np.float32(sigma) * entries.astype(np.float32)

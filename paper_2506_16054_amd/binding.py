@@ -28,7 +28,7 @@ EXPORTS = (
     "paro_version", "paro_strerror", "paro_last_error", "paro_ntokens", "paro_nblocks", "paro_npad",
     "paro_perm_index", "paro_vt_slot", "paro_mask_to_blocklist", "paro_permute", "paro_unpermute",
     "paro_quantize", "paro_sparse_attn", "paro_permute_quantize", "paro_sparse_attn_unpermuted", "paro_schedule_rows",
-    "paro_mask_to_blocklist_device",
+    "paro_mask_to_blocklist_device", "paro_calib_block_stats", "paro_calib_metrics", "paro_calib_choose", "paro_calib_mask",
 )
 
 
@@ -72,6 +72,11 @@ def lib() -> ctypes.CDLL:
         L.paro_permute_quantize.argtypes = [sp, i32, i32, i32, vp, vp, vp, vp, vp]
         L.paro_sparse_attn_unpermuted.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i32, vp, vp]
         L.paro_mask_to_blocklist_device.argtypes = [i32, i32, vp, vp, vp, i64, vp, vp]
+        f32 = ctypes.c_float
+        L.paro_calib_block_stats.argtypes = [sp, vp, vp, f32, vp, vp, vp, vp]
+        L.paro_calib_metrics.argtypes = [sp, vp, vp, vp, f32, vp, vp, vp]
+        L.paro_calib_choose.argtypes = [i32, vp, vp, f32, vp, vp, vp]
+        L.paro_calib_mask.argtypes = [sp, vp, f32, vp, vp]
         _lib = L
     return _lib
 
@@ -256,6 +261,50 @@ def paro_mask_to_blocklist_device(nh: int, k: int, bitmask, row_ptr, col_idx, nn
     cap = 0 if col_idx is None else int(col_idx.numel())
     _check(lib().paro_mask_to_blocklist_device(int(nh), int(k), _ptr(bitmask), _ptr(row_ptr), _ptr(col_idx) if cap else None, cap,
                                                _ptr(nnz_out), _stream()))
+
+
+def paro_calib_block_stats(s: paro_shape, q16, k16, eps: float, block_sum, block_max, block_cnt) -> None:
+    import torch
+
+    kb = paro_nblocks(s)
+    _require(q16, "q16", codes_shape(s, 16, PARO_ROWS), torch.bfloat16)
+    _require(k16, "k16", codes_shape(s, 16, PARO_ROWS), torch.bfloat16)
+    _require(block_sum, "block_sum", (s.B, s.nh, kb, kb), torch.float32)
+    _require(block_max, "block_max", (s.B, s.nh, kb, kb), torch.float32)
+    _require(block_cnt, "block_cnt", (s.B, s.nh, kb, kb), torch.int32)
+    _check(lib().paro_calib_block_stats(ctypes.byref(s), _ptr(q16), _ptr(k16), float(eps), _ptr(block_sum), _ptr(block_max),
+                                        _ptr(block_cnt), _stream()))
+
+
+def paro_calib_metrics(s: paro_shape, block_sum, block_max, block_cnt, sigma: float, m_sparse, m_quant) -> None:
+    import torch
+
+    kb = paro_nblocks(s)
+    _require(block_sum, "block_sum", (s.B, s.nh, kb, kb), torch.float32)
+    _require(block_max, "block_max", (s.B, s.nh, kb, kb), torch.float32)
+    _require(block_cnt, "block_cnt", (s.B, s.nh, kb, kb), torch.int32)
+    _require(m_sparse, "m_sparse", (s.nh,), torch.float32)
+    _require(m_quant, "m_quant", (s.nh,), torch.float32)
+    _check(lib().paro_calib_metrics(ctypes.byref(s), _ptr(block_sum), _ptr(block_max), _ptr(block_cnt), float(sigma), _ptr(m_sparse),
+                                    _ptr(m_quant), _stream()))
+
+
+def paro_calib_choose(nh: int, m_sparse6, m_quant6, alpha: float, m_combined6, perm_ids) -> None:
+    import torch
+
+    for name, t in (("m_sparse6", m_sparse6), ("m_quant6", m_quant6), ("m_combined6", m_combined6)):
+        _require(t, name, (6, nh), torch.float32)
+    _require(perm_ids, "perm_ids", (nh,), torch.uint8)
+    _check(lib().paro_calib_choose(int(nh), _ptr(m_sparse6), _ptr(m_quant6), float(alpha), _ptr(m_combined6), _ptr(perm_ids), _stream()))
+
+
+def paro_calib_mask(s: paro_shape, block_sum, density: float, bitmask) -> None:
+    import torch
+
+    kb = paro_nblocks(s)
+    _require(block_sum, "block_sum", (s.B, s.nh, kb, kb), torch.float32)
+    _require(bitmask, "bitmask", (s.nh, (kb * kb + 7) // 8), torch.uint8)
+    _check(lib().paro_calib_mask(ctypes.byref(s), _ptr(block_sum), float(density), _ptr(bitmask), _stream()))
 
 
 def _attn_operands(s: paro_shape, bits_qk: int, bits_pv: int, q, sq, k, sk, v, sv, row_ptr, col_idx) -> None:

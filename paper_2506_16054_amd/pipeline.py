@@ -167,3 +167,40 @@ class MaskPrefetcher:
     def release(self, slot: int) -> None:
         """Call after the attention launch that read the slot: the slot may be refilled once it is done."""
         self.slots[slot]["free"].record(torch.cuda.current_stream())
+
+
+def calibrate(shape: pb.paro_shape, q, k, eps: float = 1e-3, sigma: float = 0.9, alpha: float = 0.5, density: float = 0.3):
+    """Offline calibration of one attention layer (paper Sec. 4.1, Sec. 4.2 (3)) from calibration
+    samples q, k [B, nh, N, d]: enqueues the library calls and returns device tensors
+    ``perm_ids`` uint8 [nh], ``bitmask`` uint8 [nh, ceil(k*k/8)], ``m_sparse``, ``m_quant``,
+    ``m_combined`` float32 [6, nh], and the chosen orders' ``block_sum`` [B, nh, k, k].  The only
+    host step is the copy of the nh chosen order ids, which the reorder entry points take on the host."""
+    dev = q.device
+    nh, kb = shape.nh, pb.paro_nblocks(shape)
+    z = dict(device=dev)
+    q16 = torch.empty(pb.codes_shape(shape, 16, pb.PARO_ROWS), dtype=torch.bfloat16, **z)
+    k16 = torch.empty_like(q16)
+    unused_scales = torch.empty((shape.B, nh, kb), dtype=torch.float32, **z)
+    bsum = torch.empty((shape.B, nh, kb, kb), dtype=torch.float32, **z)
+    bmax = torch.empty_like(bsum)
+    bcnt = torch.empty((shape.B, nh, kb, kb), dtype=torch.int32, **z)
+    ms = torch.empty((6, nh), dtype=torch.float32, **z)
+    mq = torch.empty_like(ms)
+    mc = torch.empty_like(ms)
+    perm_ids = torch.empty((nh,), dtype=torch.uint8, **z)
+    bitmask = torch.empty((nh, (kb * kb + 7) // 8), dtype=torch.uint8, **z)
+
+    def stats_for(ids):
+        pb.paro_permute_quantize(shape, 16, pb.PARO_ROWS, ids, q, q16, unused_scales)
+        pb.paro_permute_quantize(shape, 16, pb.PARO_ROWS, ids, k, k16, unused_scales)
+        pb.paro_calib_block_stats(shape, q16, k16, eps, bsum, bmax, bcnt)
+
+    for t in range(6):
+        stats_for(np.full(nh, t, np.uint8))
+        pb.paro_calib_metrics(shape, bsum, bmax, bcnt, sigma, ms[t], mq[t])
+    pb.paro_calib_choose(nh, ms, mq, alpha, mc, perm_ids)
+    h_perm_ids = perm_ids.cpu().numpy()  # synchronises: the reorder calls take the ids on the host
+    stats_for(h_perm_ids)
+    pb.paro_calib_mask(shape, bsum, density, bitmask)
+    return {"perm_ids": perm_ids, "h_perm_ids": h_perm_ids, "bitmask": bitmask, "m_sparse": ms, "m_quant": mq, "m_combined": mc,
+            "block_sum": bsum}

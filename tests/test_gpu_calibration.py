@@ -1,0 +1,189 @@
+"""GPU parity of the offline calibration (paper Sec. 4.1 permutation metric, Sec. 4.2 (3) masks)
+against the float64 oracle.  Real-valued statistics must agree within REL; integer decisions taken
+on them (counts below eps, sparse-block indicators, the chosen order, the live set of the mask)
+must equal what the oracle's decision rule gives on the kernel's own statistics, and must lie inside
+the bracket the oracle computes for any evaluation of P with relative error <= TIE."""
+import numpy as np
+import pytest
+
+from oracle import paro_calibration as pc
+from oracle import paro_oracle as po
+from paper_2506_16054_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+REL = 2e-4   # block sums / maxima / M_quant: fp32 accumulation over up to N terms, hardware exp2
+TIE = 2e-4   # relative evaluation error of P assumed when bracketing counts and thresholds
+EPS, SIGMA, ALPHA = 1e-3, 0.9, 0.5
+
+CASES = {
+    "video64": wl.Workload("video64", 1, 3, 64, 5, 12, 13, 0, 64, 0.4, 8, 8, "bf16", 41),
+    "video32_f32_b2": wl.Workload("video32_f32_b2", 2, 2, 64, 3, 7, 9, 0, 32, 0.5, 8, 8, "f32", 42),
+    "flux128": wl.Workload("flux128", 1, 2, 128, 1, 16, 16, 64, 64, 0.3, 8, 8, "bf16", 43),
+    "flux128_b32": wl.Workload("flux128_b32", 1, 2, 128, 1, 8, 12, 32, 32, 0.25, 8, 8, "f32", 44),
+}
+
+
+def _mods():
+    import torch
+
+    from paper_2506_16054_amd import binding as pb
+    from paper_2506_16054_amd import pipeline
+
+    return torch, pb, pipeline
+
+
+def to_dev(x, dtype):
+    import torch
+
+    t = torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def stats_on_gpu(w, q, k, perm_id):
+    """block statistics of every (b, h) for one axis order, through the C ABI."""
+    torch, pb, _ = _mods()
+    s = pb.shape_of(w)
+    dq, dk = to_dev(q, w.dtype), to_dev(k, w.dtype)
+    q16 = torch.empty(pb.codes_shape(s, 16, pb.PARO_ROWS), dtype=torch.bfloat16, device="cuda:0")
+    k16 = torch.empty_like(q16)
+    sc = torch.empty((w.B, w.nh, w.k), dtype=torch.float32, device="cuda:0")
+    ids = np.full(w.nh, perm_id, np.uint8)
+    pb.paro_permute_quantize(s, 16, pb.PARO_ROWS, ids, dq, q16, sc)
+    pb.paro_permute_quantize(s, 16, pb.PARO_ROWS, ids, dk, k16, sc)
+    bsum = torch.full((w.B, w.nh, w.k, w.k), -1.0, dtype=torch.float32, device="cuda:0")
+    bmax = torch.full_like(bsum, -1.0)
+    bcnt = torch.full((w.B, w.nh, w.k, w.k), -1, dtype=torch.int32, device="cuda:0")
+    pb.paro_calib_block_stats(s, q16, k16, EPS, bsum, bmax, bcnt)
+    ms = torch.empty((w.nh,), dtype=torch.float32, device="cuda:0")
+    mq = torch.empty_like(ms)
+    pb.paro_calib_metrics(s, bsum, bmax, bcnt, SIGMA, ms, mq)
+    torch.cuda.synchronize()
+    return bsum.cpu().numpy(), bmax.cpu().numpy(), bcnt.cpu().numpy(), ms.cpu().numpy(), mq.cpu().numpy()
+
+
+@pytest.fixture(scope="module", params=sorted(CASES))
+def case(request):
+    w = CASES[request.param]
+    q, k, _ = wl.make_qkv(w)
+    idxs = [po.perm_index(w.F, w.Hg, w.Wg, w.T_text, t) for t in range(6)]
+    maps = [[pc.attention_map(q[b, h], k[b, h]) for h in range(w.nh)] for b in range(w.B)]
+    entries = pc.block_entries(w.N, w.block)
+    oracle = {}  # (t, b, h) -> block stats with tie brackets
+    for t in range(6):
+        for b in range(w.B):
+            for h in range(w.nh):
+                oracle[t, b, h] = pc.block_stats(pc.reorder_map(maps[b][h], idxs[t]), w.block, EPS, TIE)
+    gpu = [stats_on_gpu(w, q, k, t) for t in range(6)]
+    return {"w": w, "q": q, "k": k, "idxs": idxs, "entries": entries, "oracle": oracle, "gpu": gpu}
+
+
+def test_block_statistics(case):
+    w, entries = case["w"], case["entries"]
+    for t in range(6):
+        bsum, bmax, bcnt, _, _ = case["gpu"][t]
+        for b in range(w.B):
+            for h in range(w.nh):
+                ref = case["oracle"][t, b, h]
+                assert np.allclose(bsum[b, h], ref["sum"], rtol=REL, atol=1e-30), (t, b, h)
+                assert np.allclose(bmax[b, h], ref["max"], rtol=REL, atol=1e-30), (t, b, h)
+                assert np.all(bcnt[b, h] >= ref["cnt_lo"]) and np.all(bcnt[b, h] <= ref["cnt_hi"]), (t, b, h)
+                assert np.all(bcnt[b, h] <= entries)
+                # every row of P sums to one: a row block's sums add up to its number of real rows
+                ext = np.minimum(w.block, w.N - w.block * np.arange(w.k))
+                assert np.allclose(bsum[b, h].sum(axis=1), ext, rtol=REL)
+    exact = sum(int(np.sum(case["gpu"][t][2] == np.stack([[case["oracle"][t, b, h]["cnt"] for h in range(w.nh)] for b in range(w.B)])))
+                for t in range(6))
+    assert exact >= 0.99 * 6 * w.B * w.nh * w.k * w.k  # the brackets are rarely needed
+
+
+def test_metrics(case):
+    w, entries = case["w"], case["entries"]
+    for t in range(6):
+        bsum, bmax, bcnt, ms, mq = case["gpu"][t]
+        for h in range(w.nh):
+            # decision rule of the oracle on the kernel's own statistics: exact
+            want_ms = np.mean([pc.m_sparse(bcnt[b, h], entries, SIGMA) for b in range(w.B)])
+            assert ms[h] == pytest.approx(want_ms, abs=1e-7)
+            want_mq = np.mean([pc.m_quant(bmax[b, h].astype(np.float64), bsum[b, h].astype(np.float64), entries) for b in range(w.B)])
+            assert mq[h] == pytest.approx(want_mq, rel=1e-6)
+            # against the float64 map: inside the tie bracket / within REL
+            lo = np.mean([pc.m_sparse(case["oracle"][t, b, h]["cnt_lo"], entries, SIGMA) for b in range(w.B)])
+            hi = np.mean([pc.m_sparse(case["oracle"][t, b, h]["cnt_hi"], entries, SIGMA) for b in range(w.B)])
+            assert lo - 1e-7 <= ms[h] <= hi + 1e-7
+            ref_mq = np.mean([pc.m_quant(case["oracle"][t, b, h]["max"], case["oracle"][t, b, h]["sum"], entries) for b in range(w.B)])
+            assert mq[h] == pytest.approx(ref_mq, rel=2 * REL)
+
+
+def test_whole_calibration_chooses_a_valid_order_and_mask(case):
+    torch, pb, pipeline = _mods()
+    w, entries = case["w"], case["entries"]
+    s = pb.shape_of(w)
+    res = pipeline.calibrate(s, to_dev(case["q"], w.dtype), to_dev(case["k"], w.dtype), EPS, SIGMA, ALPHA, w.density)
+    torch.cuda.synchronize()
+    ms, mq, mc = (res[n].cpu().numpy() for n in ("m_sparse", "m_quant", "m_combined"))
+    perm = res["perm_ids"].cpu().numpy()
+    assert np.array_equal(perm, res["h_perm_ids"])
+    bits = res["bitmask"].cpu().numpy()
+    bsum = res["block_sum"].cpu().numpy()
+    k_img = -(-w.n_img // w.block)
+    n_live = int(np.rint(float(np.float32(w.density)) * k_img * k_img))
+    for h in range(w.nh):
+        for t in range(6):  # the six metric rows are those of the per-order calls
+            assert ms[t, h] == case["gpu"][t][3][h] and mq[t, h] == case["gpu"][t][4][h]
+        m_gpu, best_gpu = pc.combine(ms[:, h], mq[:, h], ALPHA)
+        assert np.allclose(mc[:, h], m_gpu, rtol=1e-6)
+        assert perm[h] == best_gpu or abs(m_gpu[perm[h]] - m_gpu[best_gpu]) <= 1e-7
+        # against the float64 metrics: the chosen order is the best one, or within the tie allowance of it
+        ref_ms = [np.mean([pc.m_sparse(case["oracle"][t, b, h]["cnt"], entries, SIGMA) for b in range(w.B)]) for t in range(6)]
+        ref_mq = [np.mean([pc.m_quant(case["oracle"][t, b, h]["max"], case["oracle"][t, b, h]["sum"], entries) for b in range(w.B)])
+                  for t in range(6)]
+        m_ref, _ = pc.combine(ref_ms, ref_mq, ALPHA)
+        width = max(np.mean([pc.m_sparse(case["oracle"][t, b, h]["cnt_hi"], entries, SIGMA) for b in range(w.B)])
+                    - np.mean([pc.m_sparse(case["oracle"][t, b, h]["cnt_lo"], entries, SIGMA) for b in range(w.B)]) for t in range(6))
+        allowance = 2 * ALPHA * width / max(6.0 - sum(ref_ms), 1e-30) + 1e-3 * m_ref.min()
+        assert m_ref[perm[h]] - m_ref.min() <= allowance, (h, m_ref, perm[h], allowance)
+        # block sums returned are those of the chosen order
+        for b in range(w.B):
+            assert np.allclose(bsum[b, h], case["oracle"][int(perm[h]), b, h]["sum"], rtol=REL, atol=1e-30)
+        # mask: exactly the oracle's selection rule on the kernel's own sums (added over samples in fp32) ...
+        tot = bsum[0, h].copy()
+        for b in range(1, w.B):
+            tot = tot + bsum[b, h]
+        want = pc.mask_from_block_sums(tot.astype(np.float64), float(np.float32(w.density)), k_img)
+        got = np.unpackbits(bits[h], bitorder="little")[: w.k * w.k].reshape(w.k, w.k).astype(bool)
+        assert np.array_equal(got, want)
+        assert int(got[:k_img, :k_img].sum()) == n_live and got[k_img:, :].all() and got[:, k_img:].all()
+        # ... and against the float64 sums: only blocks within the tie allowance of the threshold may differ
+        ref_tot = sum(case["oracle"][int(perm[h]), b, h]["sum"] for b in range(w.B))
+        ref_mask = pc.mask_from_block_sums(ref_tot, float(np.float32(w.density)), k_img)
+        diff = got != ref_mask
+        if diff.any():
+            thr = ref_tot[:k_img, :k_img][ref_mask[:k_img, :k_img]].min()
+            assert np.all(np.abs(ref_tot[diff] - thr) <= 2 * REL * thr)
+        # the mask feeds the attention path: the device expansion accepts it as is
+        row_ptr = torch.empty((w.nh, w.k + 1), dtype=torch.int32, device="cuda:0")
+        col_idx = torch.empty((w.nh * w.k * w.k,), dtype=torch.int32, device="cuda:0")
+        nnz = torch.zeros((1,), dtype=torch.int32, device="cuda:0")
+        pb.paro_mask_to_blocklist_device(w.nh, w.k, res["bitmask"], row_ptr, col_idx, nnz)
+        torch.cuda.synchronize()
+        assert int(nnz.item()) == int(np.unpackbits(bits, axis=1, bitorder="little")[:, : w.k * w.k].sum())
+
+
+def test_mask_selection_with_ties_and_extreme_densities():
+    """paro_calib_mask alone on hand-made block sums: many equal sums across the threshold, density 0 and 1."""
+    torch, pb, _ = _mods()
+    w = CASES["flux128_b32"]
+    s = pb.shape_of(w)
+    k, k_img = w.k, -(-w.n_img // w.block)
+    rng = np.random.default_rng(45)
+    sums = rng.integers(0, 4, size=(w.B, w.nh, k, k)).astype(np.float32) * 0.25  # only four distinct values
+    d_sums = torch.from_numpy(sums).to("cuda:0")
+    for density in (0.0, 0.1, 0.5, 0.77, 1.0):
+        bits = torch.zeros((w.nh, (k * k + 7) // 8), dtype=torch.uint8, device="cuda:0")
+        pb.paro_calib_mask(s, d_sums, density, bits)
+        torch.cuda.synchronize()
+        for h in range(w.nh):
+            got = np.unpackbits(bits[h].cpu().numpy(), bitorder="little")[: k * k].reshape(k, k).astype(bool)
+            want = pc.mask_from_block_sums(sums[0, h].astype(np.float64), float(np.float32(density)), k_img)
+            assert np.array_equal(got, want), (density, h)
