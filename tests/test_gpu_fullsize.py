@@ -115,3 +115,63 @@ def test_headline_shape_bf16_mode():
 
 def test_headline_shape_all_int4():
     check_sampled(wl.WORKLOADS["cogvideox5b"].replace(name="cogvideox5b_i4i4", bits_qk=4, bits_pv=4, density=0.5, nh=8), heads=(1, 6))
+
+
+def test_headline_shape_calibration_sampled():
+    """Offline calibration (Sec. 4.1 metric, Sec. 4.2 (3) masks) at N = 17550 on 8 heads: properties that
+    hold at any size on every head; one head's metrics of one axis order against the oracle over the
+    whole map (row block by row block); sampled row blocks of the chosen orders' block sums."""
+    import time
+
+    import torch
+
+    from oracle import paro_calibration as pc
+    from paper_2506_16054_amd import binding as pb
+    from paper_2506_16054_amd import pipeline
+    from tests.test_gpu_calibration import EPS, REL, SIGMA, TIE, stats_on_gpu
+
+    w = wl.WORKLOADS["cogvideox5b"].replace(name="cogvideox5b_calib", nh=8)
+    s = pb.shape_of(w)
+    q = np.empty((1, w.nh, w.N, w.d), np.float32)
+    k = np.empty_like(q)
+    for h in range(w.nh):
+        q[0, h], k[0, h], _ = wl.make_head_qkv(w, 0, h)
+    dq, dk = (torch.from_numpy(x).to("cuda:0").to(torch.bfloat16) for x in (q, k))
+    pipeline.calibrate(s, dq, dk, EPS, SIGMA, 0.5, w.density)  # warm-up
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    res = pipeline.calibrate(s, dq, dk, EPS, SIGMA, 0.5, w.density)
+    torch.cuda.synchronize()
+    print("calibration of %d heads at N=%d: %.1f ms" % (w.nh, w.N, (time.perf_counter() - t0) * 1e3))
+    bsum = res["block_sum"].cpu().numpy()
+    perm = res["h_perm_ids"]
+    bits = res["bitmask"].cpu().numpy()
+    ext = np.minimum(w.block, w.N - w.block * np.arange(w.k))
+    n_live = int(np.rint(float(np.float32(w.density)) * w.k * w.k))
+    for h in range(w.nh):
+        assert np.allclose(bsum[0, h].sum(axis=1), ext, rtol=REL)
+        got = np.unpackbits(bits[h], bitorder="little")[: w.k * w.k].reshape(w.k, w.k).astype(bool)
+        assert int(got.sum()) == n_live
+        assert np.array_equal(got, pc.mask_from_block_sums(bsum[0, h].astype(np.float64), float(np.float32(w.density)), w.k))
+    for h in (1, 6):
+        idx = po.perm_index(w.F, w.Hg, w.Wg, w.T_text, int(perm[h]))
+        for i in (0, 137, w.k - 1):
+            ref = pc.row_block_stats(q[0, h], k[0, h], idx, i, w.block, EPS)
+            assert np.allclose(bsum[0, h, i], ref["sum"][0], rtol=REL, atol=1e-30), (h, i)
+    # one head, one order, the whole map
+    h, t = 3, 4
+    g_sum, g_max, g_cnt, g_ms, g_mq = stats_on_gpu(w, q, k, t)
+    idx = po.perm_index(w.F, w.Hg, w.Wg, w.T_text, t)
+    entries = pc.block_entries(w.N, w.block)
+    lo = np.zeros((w.k, w.k), np.int64)
+    hi = np.zeros_like(lo)
+    r_sum = np.zeros((w.k, w.k))
+    r_max = np.zeros((w.k, w.k))
+    for i in range(w.k):
+        st = pc.row_block_stats(q[0, h], k[0, h], idx, i, w.block, EPS, TIE)
+        lo[i], hi[i], r_sum[i], r_max[i] = st["cnt_lo"][0], st["cnt_hi"][0], st["sum"][0], st["max"][0]
+    assert np.all(g_cnt[0, h] >= lo) and np.all(g_cnt[0, h] <= hi)
+    assert np.allclose(g_sum[0, h], r_sum, rtol=REL, atol=1e-30) and np.allclose(g_max[0, h], r_max, rtol=REL, atol=1e-30)
+    assert pc.m_sparse(lo, entries, SIGMA) - 1e-7 <= g_ms[h] <= pc.m_sparse(hi, entries, SIGMA) + 1e-7
+    assert g_mq[h] == pytest.approx(pc.m_quant(r_max, r_sum, entries), rel=2 * REL)
+    print("head %d order %d: M_sparse %.4f M_quant %.2f" % (h, t, g_ms[h], g_mq[h]))
