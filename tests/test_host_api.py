@@ -123,6 +123,22 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
     assert L.paro_mask_to_blocklist_device(2, 4, fake, fake, None, 16, None, None) == pb.PARO_EINVAL
     assert L.paro_mask_to_blocklist_device(2, 4, fake, fake, fake, -1, None, None) == pb.PARO_EINVAL
     assert L.paro_mask_to_blocklist_device(200, 30000, fake, fake, fake, 16, None, None) == pb.PARO_EINVAL
+    # offline calibration
+    f = ctypes.c_float
+    assert L.paro_calib_block_stats(ctypes.byref(s), fake, fake, f(0.0), fake, fake, fake, None) == pb.PARO_EINVAL
+    assert L.paro_calib_block_stats(ctypes.byref(s), None, fake, f(1e-3), fake, fake, fake, None) == pb.PARO_EINVAL
+    assert L.paro_calib_block_stats(ctypes.byref(s), ctypes.c_void_p(0x1008), fake, f(1e-3), fake, fake, fake, None) == pb.PARO_EINVAL
+    assert L.paro_calib_metrics(ctypes.byref(s), fake, fake, fake, f(1.5), fake, fake, None) == pb.PARO_EINVAL
+    assert L.paro_calib_metrics(ctypes.byref(s), fake, fake, None, f(0.9), fake, fake, None) == pb.PARO_EINVAL
+    assert L.paro_calib_choose(0, fake, fake, f(0.5), fake, fake, None) == pb.PARO_EINVAL
+    assert L.paro_calib_choose(4, fake, fake, f(-0.1), fake, fake, None) == pb.PARO_EINVAL
+    assert L.paro_calib_choose(4, fake, None, f(0.5), fake, fake, None) == pb.PARO_EINVAL
+    assert L.paro_calib_mask(ctypes.byref(s), fake, f(1.2), fake, None) == pb.PARO_EINVAL
+    assert L.paro_calib_mask(ctypes.byref(s), None, f(0.3), fake, None) == pb.PARO_EINVAL
+    ragged_text = pb.make_shape(1, 2, 64, 1, 5, 5, 8, 32)  # 25 image tokens do not fill whole blocks before the text
+    assert L.paro_calib_mask(ctypes.byref(ragged_text), fake, f(0.3), fake, None) == pb.PARO_EUNSUPPORTED
+    huge = pb.make_shape(1, 1, 64, 40, 32, 32, 0, 64)  # k = 640: k*k exceeds the mask kernel's LDS bit array
+    assert L.paro_calib_mask(ctypes.byref(huge), fake, f(0.3), fake, None) == pb.PARO_EUNSUPPORTED
 
 
 def test_fused_entry_points_validate_on_the_host():
