@@ -40,6 +40,35 @@ def recorded_traffic(workload: str):
         return None
 
 
+def recorded_valu_instructions(workload: str):
+    """Vector-ALU wave instructions per launch of the attention kernel (rocprofv3 SQ_INSTS_VALU, summarised
+    under profiles/), or None."""
+    import re
+
+    path = os.path.join(ROOT, "profiles", "attn_i8_%s_sq_counters.md" % workload)
+    try:
+        m = re.search(r"\| SQ_INSTS_VALU \| ([0-9.e+]+) \|", open(path).read())
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def sustained_mfma_rate(pb, torch, bits):
+    """TOP/s (or TFLOP/s) of a kernel that only issues dense matrix instructions: the rate this GPU
+    sustains, as opposed to the published peak."""
+    out = torch.empty(4096, dtype=torch.int32, device="cuda:0")
+    for _ in range(3):
+        pb.paro_probe_mfma(bits, 4000, out)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    ops = 0
+    for _ in range(10):
+        ops += pb.paro_probe_mfma(bits, 4000, out)
+    e1.record()
+    torch.cuda.synchronize()
+    return ops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -283,6 +312,8 @@ def main():
     algorithmic_bytes = int(w.B * w.nh * w.npad * w.d * (2 * qk_bytes + v_bytes) + w.B * w.nh * w.N * w.d * (2 if w.dtype == "bf16" else 4))
     peak = PEAK_INT8_TOPS if quantized else PEAK_BF16_TFLOPS
     achieved = live_ops / (attn_avg * 1e-3) / 1e12
+    sustained = sustained_mfma_rate(pb, torch, 8 if quantized else 16)
+    valu = recorded_valu_instructions(w.name) if quantized else None
     out = {
         "metric": "dense_equivalent_TOPS",
         "value": dense_ops / (ms_per_step * 1e-3) / 1e12,
@@ -320,8 +351,22 @@ def main():
             "traffic": recorded_traffic(w.name),
             "traffic_unit": "bytes per launch (HBM read + write, rocprofv3 counters scaled by a known copy)",
             "algorithmic_bytes": algorithmic_bytes,
+            "peak_sustained": sustained,
+            "frac_of_sustained": achieved / sustained,
+            "peak_sustained_note": "rate of a kernel that only issues this matrix instruction, measured in this run",
         },
     }
+    if valu is not None:
+        # what actually binds the kernel at d = 64: vector-ALU issue.  Peak: 157.3 TFLOP/s of fp32 vector
+        # math = 2 flop x 64 lanes per wave instruction -> 1.229e12 wave instructions per second.
+        peak_wave_inst = 157.3e12 / 128.0
+        out["valu_issue"] = {
+            "wave_instructions_per_launch": valu,
+            "achieved_per_s": valu / (attn_avg * 1e-3),
+            "peak_per_s": peak_wave_inst,
+            "frac": valu / (attn_avg * 1e-3) / peak_wave_inst,
+            "note": "instruction count from profiles/ (SQ_INSTS_VALU); exp2, conversions and cross-lane moves issue at 1/2 to 1/4 of the fp32 rate",
+        }
     if prefetch is not None:
         out["mask_prefetch"] = prefetch
     if cpu is not None:

@@ -268,6 +268,15 @@ int paro_calib_choose(int nh, const float* m_sparse6, const float* m_quant6, flo
 int paro_calib_mask(const paro_shape* s, const float* block_sum, float density, uint8_t* bitmask,
                     void* stream);
 
+/* ---- measurement aid ------------------------------------------------------------------------
+ * Enqueues a kernel that does nothing but issue dense matrix instructions on register operands
+ * (four wavefronts per SIMD on 256 compute units, `iters` rounds of four independent
+ * v_mfma_i32_32x32x32_i8 (bits 8) or v_mfma_f32_32x32x16_bf16 (bits 16) each) and returns the
+ * number of operations (2 per multiply-add) it performs, or a negative status.  Timed by the
+ * caller, it gives the matrix rate this GPU sustains, to quote beside the published peak.
+ *   out  int32 [out_len], out_len >= 4096: one checksum per wavefront (keeps the work alive) */
+int64_t paro_probe_mfma(int bits, int iters, int32_t* out, int64_t out_len, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

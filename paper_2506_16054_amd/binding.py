@@ -29,6 +29,7 @@ EXPORTS = (
     "paro_perm_index", "paro_vt_slot", "paro_mask_to_blocklist", "paro_permute", "paro_unpermute",
     "paro_quantize", "paro_sparse_attn", "paro_permute_quantize", "paro_sparse_attn_unpermuted", "paro_schedule_rows",
     "paro_mask_to_blocklist_device", "paro_calib_block_stats", "paro_calib_metrics", "paro_calib_choose", "paro_calib_mask",
+    "paro_probe_mfma",
 )
 
 
@@ -77,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.paro_calib_metrics.argtypes = [sp, vp, vp, vp, f32, vp, vp, vp]
         L.paro_calib_choose.argtypes = [i32, vp, vp, f32, vp, vp, vp]
         L.paro_calib_mask.argtypes = [sp, vp, f32, vp, vp]
+        L.paro_probe_mfma.restype = i64
+        L.paro_probe_mfma.argtypes = [i32, i32, vp, i64, vp]
         _lib = L
     return _lib
 
@@ -305,6 +308,17 @@ def paro_calib_mask(s: paro_shape, block_sum, density: float, bitmask) -> None:
     _require(block_sum, "block_sum", (s.B, s.nh, kb, kb), torch.float32)
     _require(bitmask, "bitmask", (s.nh, (kb * kb + 7) // 8), torch.uint8)
     _check(lib().paro_calib_mask(ctypes.byref(s), _ptr(block_sum), float(density), _ptr(bitmask), _stream()))
+
+
+def paro_probe_mfma(bits: int, iters: int, out) -> int:
+    """Enqueues the matrix-rate probe; returns the number of operations it performs."""
+    import torch
+
+    _require(out, "out", None, torch.int32)
+    ops = lib().paro_probe_mfma(int(bits), int(iters), _ptr(out), int(out.numel()), _stream())
+    if ops < 0:
+        _check(int(ops))
+    return int(ops)
 
 
 def _attn_operands(s: paro_shape, bits_qk: int, bits_pv: int, q, sq, k, sk, v, sv, row_ptr, col_idx) -> None:

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIBDIR = os.path.join(PKG, "lib")
 LIBPATH = os.path.join(LIBDIR, "libparo.so")
-SOURCES = ("host_api.cpp", "permute.hip", "quantize.hip", "blocklist.hip", "calibrate.hip", "sparse_attn.hip")
+SOURCES = ("host_api.cpp", "permute.hip", "quantize.hip", "blocklist.hip", "calibrate.hip", "probe.hip", "sparse_attn.hip")
 
 # -packed-fp32-ops is switched off on purpose: all float math here is scalar per lane.
 HIPCC_FLAGS = [
