@@ -1,0 +1,22 @@
+"""Host-side logic of the pipeline module that needs no GPU."""
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_2506_16054_amd.pipeline import shared_mask_index
+
+
+def test_timestep_mask_sharing_first_half_distinct_rest_common():
+    # paper Sec. 4.2 (1): distinct masks for the first half of the timesteps, one common mask afterwards
+    T = 30  # the sampling schedule the paper uses for CogVideoX
+    idx = [shared_mask_index(t, T) for t in range(T)]
+    assert idx[:15] == list(range(15))
+    assert set(idx[15:]) == {15}
+    assert len(set(idx)) == 16
+    assert [shared_mask_index(t, 5) for t in range(5)] == [0, 1, 2, 3, 3]
+    assert [shared_mask_index(t, 1) for t in range(1)] == [0]
+    assert [shared_mask_index(t, 2) for t in range(2)] == [0, 1]
+    with pytest.raises(ValueError):
+        shared_mask_index(5, 5)
+    with pytest.raises(ValueError):
+        shared_mask_index(-1, 5)
