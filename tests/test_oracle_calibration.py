@@ -50,6 +50,8 @@ def test_uniform_and_one_hot_blocks_closed_forms():
     assert np.allclose(pc.psi_blocks(st["max"], st["sum"], ent), 1.0)
     st = pc.block_stats(p, b, 0.1)  # 1/12 < 0.1: every entry is "small"
     assert np.all(st["cnt"] == b * b) and pc.m_sparse(st["cnt"], ent, 0.9) == 1.0
+    quarter = np.full((4, 4), 0.25)
+    assert np.all(pc.block_stats(quarter, 2, 0.25)["cnt"] == 0)  # the inequality of Eq. (M_sparse) is strict
     one = np.zeros((n, n))
     one[5, 9] = 0.7  # block (1, 2)
     st = pc.block_stats(one, b, 1e-3)
