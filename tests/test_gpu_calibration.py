@@ -187,3 +187,30 @@ def test_mask_selection_with_ties_and_extreme_densities():
             got = np.unpackbits(bits[h].cpu().numpy(), bitorder="little")[: k * k].reshape(k, k).astype(bool)
             want = pc.mask_from_block_sums(sums[0, h].astype(np.float64), float(np.float32(density)), k_img)
             assert np.array_equal(got, want), (density, h)
+
+
+def test_calibration_output_drives_the_attention_path_end_to_end():
+    """Order ids and masks come from the GPU calibration, the block list from the device-side expansion
+    of that mask (no host copy of the mask in the path); the attention output must match the oracle run
+    with the same order ids and mask, to the bar of the attention parity tests."""
+    torch, pb, pipeline = _mods()
+    from tests.helpers import check_attention, oracle_head
+    from tests.test_gpu_parity import MAX_ABS, REL_L2
+
+    w = CASES["video64"]
+    s = pb.shape_of(w)
+    q, k, v = wl.make_qkv(w)
+    dq, dk, dv = (to_dev(x, w.dtype) for x in (q, k, v))
+    res = pipeline.calibrate(s, dq, dk, EPS, SIGMA, ALPHA, w.density)
+    perm = res["h_perm_ids"]
+    row_ptr = torch.empty((w.nh, w.k + 1), dtype=torch.int32, device="cuda:0")
+    col_idx = torch.empty((w.nh * w.k * w.k,), dtype=torch.int32, device="cuda:0")
+    pb.paro_mask_to_blocklist_device(w.nh, w.k, res["bitmask"], row_ptr, col_idx)
+    bits = res["bitmask"].cpu().numpy()
+    pa = pipeline.ParoAttention(s, perm, bits, w.bits_qk, w.bits_pv, torch.bfloat16)
+    pa.use_blocklist(row_ptr, col_idx, None)
+    o = pa.run_fused(dq, dk, dv).float().cpu().numpy()
+    ref_ptr, ref_cols = po.mask_to_blocklist(bits, w.nh, w.k)
+    for h in range(w.nh):
+        ref = oracle_head(w, q[0, h], k[0, h], v[0, h], perm[h], ref_ptr[h], ref_cols)
+        check_attention(o[0, h], ref["o"], po.unpermute(ref["flip_risk"], ref["idx"]), MAX_ABS, REL_L2, "calibrated head %d" % h)
