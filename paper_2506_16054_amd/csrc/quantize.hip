@@ -61,7 +61,11 @@ __global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ x
     constexpr int OUT_BYTES = ELEMS * BITS / 8;
     constexpr float QMAX = BITS == 4 ? 7.0f : 127.0f;
     // LDS staging of the transposed tile: bytes for 8- and 4-bit codes, 16-bit words for bf16.
-    constexpr int STAGE_BYTES = LAYOUT == PARO_VT ? ELEMS * (BITS == 16 ? 2 : 1) : 16;
+    // Rows of the staged transposed tile (one channel each) are 4 bytes longer than the block for the
+    // integer codes, so that the byte stores of the 8 lanes that hold one token's 64 channels fall into
+    // different LDS banks.
+    constexpr int SSTR = BITS == 16 ? BLK : BLK + 4;
+    constexpr int STAGE_BYTES = LAYOUT == PARO_VT ? D * SSTR * (BITS == 16 ? 2 : 1) : 16;
     __shared__ __attribute__((aligned(16))) uint8_t stage[STAGE_BYTES];
     __shared__ float wave_amax[4];
 
@@ -109,6 +113,19 @@ __global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ x
         if (amax > 0.0f) scale = amax / QMAX;  // correctly rounded binary32 divide
     }
     if (tid == 0) scales[group] = scale;
+    // x / scale, correctly rounded, for the many elements that share one divisor: with y the correctly
+    // rounded reciprocal of the divisor, q0 = RN(x y), r = x - q0 scale (one fma), the value
+    // RN(q0 + r y) is the correctly rounded quotient (Markstein's division theorem).  The theorem
+    // excludes divisors whose significand is all ones, and the reciprocal must be a normal number:
+    // those groups take the generic divide.  Either way the code equals rint(fl32(x / scale)).
+    const float inv_scale = 1.0f / scale;
+    const bool generic_divide = (__float_as_uint(scale) & 0x7fffffu) == 0x7fffffu || !(scale > 1e-20f && scale < 1e20f);
+    auto quotient = [&](float v) {
+        if (generic_divide) return v / scale;
+        const float q0 = v * inv_scale;
+        const float rem = fmaf(-q0, scale, v);
+        return fmaf(rem, inv_scale, q0);
+    };
 
 #pragma unroll
     for (int it = 0; it < IT; ++it) {
@@ -133,7 +150,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ x
             int q[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float r = rintf(x[it][e] / scale);  // v_rndne_f32: round half to even
+                const float r = rintf(quotient(x[it][e]));  // v_rndne_f32: round half to even
                 q[e] = (int)fminf(fmaxf(r, -QMAX), QMAX);
             }
             if constexpr (LAYOUT == PARO_ROWS) {
@@ -151,7 +168,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ x
             } else {
                 const int slot = vt_slot(row);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) stage[(c0 + e) * BLK + slot] = (uint8_t)q[e];
+                for (int e = 0; e < 8; ++e) stage[(c0 + e) * SSTR + slot] = (uint8_t)q[e];
             }
         }
     }
@@ -162,8 +179,14 @@ __global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ x
             // 8 consecutive slots of one channel -> 4 bytes: byte t = slot t | slot 4+t << 4
             constexpr int GROUPS = ELEMS / 8;
             for (int g = tid; g < GROUPS; g += 256) {
-                const uint2 s = *(const uint2*)(stage + g * 8);
-                *(unsigned*)(out + (size_t)g * 4) = (s.x & 0x0f0f0f0fu) | ((s.y & 0x0f0f0f0fu) << 4);
+                const unsigned* src = (const unsigned*)(stage + (g / (BLK / 8)) * SSTR + (g % (BLK / 8)) * 8);
+                *(unsigned*)(out + (size_t)g * 4) = (src[0] & 0x0f0f0f0fu) | ((src[1] & 0x0f0f0f0fu) << 4);
+            }
+        } else if constexpr (BITS == 8) {
+            constexpr int VEC = ELEMS / 16;
+            for (int v = tid; v < VEC; v += 256) {
+                const unsigned* src = (const unsigned*)(stage + (v / (BLK / 16)) * SSTR + (v % (BLK / 16)) * 16);
+                ((uint4*)out)[v] = make_uint4(src[0], src[1], src[2], src[3]);
             }
         } else {
             constexpr int VEC = STAGE_BYTES / 16;

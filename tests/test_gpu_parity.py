@@ -248,6 +248,70 @@ def test_quantize_all_modes_ragged(dtype, bits, layout):
         assert np.array_equal(got_s[0, h], ref_s)
 
 
+def _amax_with_all_ones_scale(rng, qmax):
+    """A float32 absmax whose binary32 quotient by qmax has an all-ones significand."""
+    while True:
+        e = int(rng.integers(-8, 8))
+        target = np.float32((2.0 - 2.0 ** -23) * 2.0 ** e)
+        a = np.float32(target * np.float32(qmax))
+        for _ in range(64):
+            if (np.float32(a / np.float32(qmax)).view(np.uint32) & np.uint32(0x7FFFFF)) == np.uint32(0x7FFFFF):
+                return a
+            a = np.nextafter(a, np.float32(0), dtype=np.float32)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_quantize_codes_are_the_correctly_rounded_quotient_in_hard_cases(bits):
+    """The code is rint(fl32(x / scale)) bit for bit: groups with huge and tiny magnitudes, scales whose
+    significand is all ones, and elements placed on and next to rounding ties of the quotient."""
+    torch, pb = _torch(), _pb()
+    rng = np.random.default_rng(300 + bits)
+    qmax = po.qmax_of(bits)
+    B, nh, d, block = 1, 2, 64, 64
+    F, H, W = 4, 8, 16  # N = 512 = 8 blocks
+    s = pb.make_shape(B, nh, d, F, H, W, 0, block)
+    n = npad = 512
+    k = 8
+    x = np.zeros((B, nh, npad, d), np.float32)
+    mags = [2.0 ** -60, 2.0 ** -30, 1.0, 2.0 ** 30, 2.0 ** 60, 3e-39, 1.0, 1.0]
+    for h in range(nh):
+        for g in range(k):
+            blk = rng.standard_normal((block, d)).astype(np.float32)
+            amax = np.float32(np.abs(blk).max())
+            if g >= 6:  # scale with an all-ones significand
+                amax_new = _amax_with_all_ones_scale(rng, qmax)
+                blk = (blk * (amax_new / amax) * np.float32(0.999)).astype(np.float32)
+                blk[0, 0] = amax_new
+                scale = np.float32(amax_new / np.float32(qmax))
+            else:
+                blk = (blk * np.float32(mags[g])).astype(np.float32)
+                scale = np.float32(np.abs(blk).max() / np.float32(qmax))
+            # ties of the quotient and their neighbours, without raising the absmax
+            for i in range(1, 40):
+                c = int(rng.integers(0, qmax - 1))
+                t = np.float32(np.float32(c + 0.5) * scale)
+                for j, v in enumerate((np.nextafter(t, np.float32(0)), t, np.nextafter(t, np.float32(np.inf)))):
+                    blk[i, 3 * (i % 20) + j] = v if rng.random() < 0.5 else -v
+            x[0, h, g * block:(g + 1) * block] = blk
+    xp = to_dev(x, "f32")
+    for lay, name in ((pb.PARO_ROWS, "rows"), (pb.PARO_VT, "vt")):
+        codes = torch.full(pb.codes_shape(s, bits, lay), -1, dtype=torch.int8, device="cuda:0")
+        scales = torch.full((B, nh, k), float("nan"), dtype=torch.float32, device="cuda:0")
+        pb.paro_quantize(s, bits, lay, xp, codes, scales)
+        torch.cuda.synchronize()
+        got, got_s = host(codes), scales.cpu().numpy()
+        for h in range(nh):
+            ref_c, ref_s = po.quantize_blocks(x[0, h], n, block, qmax)
+            if name == "rows":
+                rows = unpack_rows_int4(got[0, h]) if bits == 4 else got[0, h].astype(np.int32)
+            else:
+                rows = vt_to_rows(unpack_vt_int4(got[0, h]) if bits == 4 else got[0, h].astype(np.int32), block)
+            assert np.array_equal(got_s[0, h], ref_s), name
+            bad = np.argwhere(rows != ref_c)
+            assert bad.size == 0, "%s: %d codes differ, first at %s" % (name, len(bad), bad[:3].tolist())
+        assert (np.asarray(got_s).view(np.uint32) & 0x7FFFFF == 0x7FFFFF).any()  # the all-ones case was exercised
+
+
 def test_empty_row_block_gives_zeros():
     torch, pb = _torch(), _pb()
     from paper_2506_16054_amd.pipeline import ParoAttention
