@@ -26,6 +26,11 @@
 //        which also packs four codes into one register,
 //   l  = l * 2^(m - m') + sP * rowsum(E),  sP = 2^e / qmaxP   (the P tile maximum over qmaxP)
 //   acc = acc * 2^(m - m') + (sP * sv_j) * float(Pc V_j)
+// The two running sums are held divided by 2^(m' - m_ref), m_ref being the row's maximum after its
+// first block: then the factor 2^(m - m') never has to be applied to them (the new term is
+// multiplied by 2^(m' - m_ref) instead, one scalar per row), and since the output is acc / l the
+// common factor cancels.  If a row's maximum climbs more than 64 octaves above its reference the
+// sums are brought back to the current maximum (a rare, wavefront-uniform branch).
 #include <string.h>
 
 #include <type_traits>
@@ -261,7 +266,8 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     };
 
     float m = -INFINITY;  // running row maximum, log2 units
-    float l = 0.0f;       // this lane's share of the running denominator
+    float m_ref = 0.0f;   // the maximum the stored sums are expressed against
+    float l = 0.0f;       // this lane's share of the running denominator (divided by 2^(m - m_ref))
     float acc[DT][16];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -355,8 +361,20 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
             for (int ww = 0; ww < NW; ++ww) eb = min(eb, tile_e[t & 1][ww]);
         }
         const float e = __uint_as_float(eb);
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-        const float s_p = __builtin_amdgcn_exp2f(e) * (1.0f / QMAXP);
+        if (m == -INFINITY) m_ref = m_new;  // first block of the row: its maximum becomes the reference
+        float growth = m_new - m_ref;
+        if (__builtin_amdgcn_ballot_w64(growth > 64.0f) != 0) {  // keep the stored sums far from overflow
+            const float down = __builtin_amdgcn_exp2f(-growth);
+            l *= down;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[dt][r] *= down;
+            m_ref = m_new;
+            growth = 0.0f;
+        }
+        // weight of this block's terms in the stored sums: sP * 2^(m' - m_ref)
+        const float w_blk = __builtin_amdgcn_exp2f(e + growth) * (1.0f / QMAXP);
         // exponent offset: X - m' - e + log2(qmaxP), so that the tile maximum maps to qmaxP
         const float off = LOG2_QMAXP - m_new - e;
         m = m_new;
@@ -378,18 +396,10 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
                 pf[T][qd] = (int)pk;
             }
         }
-        l = fmaf(l, alpha, rs * s_p);
+        l = fmaf(rs, w_blk, l);
 
-        // ---- O^T = alpha * O^T + (sP sv_j) V_j^T P^T; the rescale is skipped when no running
-        // maximum in this wavefront moved (the common case once the row has seen its peak)
-        const float sv_eff = s_p * sv_cur * (PVBITS == 4 ? 0.0625f : 1.0f);
-        const bool rescale = __builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0;
-        if (rescale) {
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[dt][r] *= alpha;
-        }
+        // ---- O^T += (sP sv_j 2^(m' - m_ref)) V_j^T P^T
+        const float sv_eff = w_blk * sv_cur * (PVBITS == 4 ? 0.0625f : 1.0f);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             v16i o = acc_init;
@@ -533,7 +543,11 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
         }
     };
 
-    float m = -INFINITY;
+    // The exponentials are taken against a fixed reference per row (its maximum after the first
+    // block) instead of the running maximum: P is not quantized here, so the common factor
+    // 2^(m - m_ref) of numerator and denominator cancels in acc / l and no rescaling pass is needed.
+    // A row whose maximum climbs more than 64 octaves above the reference is re-referenced.
+    float m_ref = -INFINITY;
     float l = 0.0f;
     v16f acc[DT];
 #pragma unroll
@@ -586,7 +600,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
             const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_int(mx), __float_as_int(mx), false, false);
             mx = fmaxf(__int_as_float((int)sw[0]), __int_as_float((int)sw[1]));
         }
-        const float m_new = fmaxf(m, c * mx);
+        const float ymax = c * mx;
         __syncthreads();
         if (t + 1 < cnt) lstore_v(next);
         if (((t + 2) & 63) == 0) {
@@ -595,8 +609,18 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
             cols_nxt = load_cols(cur_chunk + 1);
         }
         if (t + 2 < cnt) gload(t + 2);
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-        m = m_new;
+        if (m_ref == -INFINITY) m_ref = ymax;
+        if (__builtin_amdgcn_ballot_w64(ymax - m_ref > 64.0f) != 0) {
+            const float up = fmaxf(ymax, m_ref);
+            const float down = __builtin_amdgcn_exp2f(m_ref - up);
+            l *= down;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[dt][r] *= down;
+            m_ref = up;
+        }
+        const float m_new = m_ref;
 
         float rs = 0.0f;
         v8bf pf[KT][2];
@@ -613,15 +637,8 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
                     pf[T][u][2 * e2] = pb[0];
                     pf[T][u][2 * e2 + 1] = pb[1];
                 }
-        l = fmaf(l, alpha, rs);
+        l += rs;
 
-        const bool rescale = __builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0;
-        if (rescale) {
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[dt][r] *= alpha;
-        }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
