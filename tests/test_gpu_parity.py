@@ -312,6 +312,41 @@ def test_quantize_codes_are_the_correctly_rounded_quotient_in_hard_cases(bits):
         assert (np.asarray(got_s).view(np.uint32) & 0x7FFFFF == 0x7FFFFF).any()  # the all-ones case was exercised
 
 
+@pytest.mark.parametrize("bits", [8, 16])
+def test_row_maximum_climbing_hundreds_of_octaves(bits):
+    """Keys whose magnitude grows along the sequence make the running row maximum climb by far more
+    than 64 octaves between the first and the last live block, so the kernels have to re-reference
+    their running sums several times; a second head has the steep end first (the maximum never moves
+    after the first block)."""
+    torch, pb = _torch(), _pb()
+    from paper_2506_16054_amd.pipeline import ParoAttention
+
+    w = SMALL["video64"].replace(nh=2, perm_choice=(0, 0), bits_qk=bits, bits_pv=bits, density=1.0, dtype="f32", seed=77)
+    masks = wl.make_block_masks(w, gather_fn(w))
+    bm, row_ptr, col_idx = blocklist_for(w, masks)
+    rng = np.random.default_rng(78)
+    ramp = np.linspace(0.05, 12.0, w.N)[:, None]
+    q = np.abs(rng.standard_normal((1, 2, w.N, w.d))).astype(np.float32) * 3
+    k = np.abs(rng.standard_normal((1, 2, w.N, w.d))).astype(np.float32)
+    k[0, 0] *= ramp          # logits grow along the sequence
+    k[0, 1] *= ramp[::-1]    # logits shrink along the sequence
+    v = rng.standard_normal((1, 2, w.N, w.d)).astype(np.float32)
+    if bits == 16:
+        q, k, v = (wl.bf16_round(x) for x in (q, k, v))
+    pa = ParoAttention(pb.shape_of(w), wl.make_perm_ids(w), bm, bits, bits, torch.float32)
+    o = host(pa.run_fused(*(to_dev(x, "f32") for x in (q, k, v))))
+    torch.cuda.synchronize()
+    for h in range(2):
+        r = oracle_head(w, q[0, h], k[0, h], v[0, h], 0, row_ptr[h], col_idx)
+        # the spread of the logits of one row, in octaves, far exceeds the re-referencing threshold
+        logit = (q[0, h, :1].astype(np.float64) @ k[0, h].astype(np.float64).T) / np.sqrt(w.d) * np.log2(np.e)
+        assert logit.max() - logit.min() > 200
+        assert np.isfinite(o[0, h]).all()
+        st = check_attention(o[0, h], r["o"], po.unpermute(r["flip_risk"], r["idx"]), MAX_ABS, REL_L2_BF16 if bits == 16 else REL_L2,
+                             "steep head %d" % h)
+        assert st["rel_l2"] < 1e-3
+
+
 def test_empty_row_block_gives_zeros():
     torch, pb = _torch(), _pb()
     from paper_2506_16054_amd.pipeline import ParoAttention
