@@ -321,8 +321,8 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
                 sacc[T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf[s], sacc[T], 0, 0, 0);
             }
         }
-        // Raw accumulator value of a masked logit: it loses every maximum, and read as a float
-        // it is +0, i.e. a logit of -1.5 * 2^23 * c whose exponential is 0.
+        // Raw accumulator value of a masked logit: it loses every maximum (real values carry the
+        // accumulator bias); its exponential is forced to zero below.
         constexpr int kMaskedS = 0;
         if constexpr (TAIL) {  // keys past N never receive probability mass
             const int nkeys = a.n_tokens - (a.kblocks - 1) * BLK;
@@ -389,7 +389,10 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
                 unsigned pk = 0;
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
-                    const float ev = __builtin_amdgcn_exp2f(fmaf(int_result(sacc[T][4 * qd + p]), c, off));
+                    float ev = __builtin_amdgcn_exp2f(fmaf(int_result(sacc[T][4 * qd + p]), c, off));
+                    if constexpr (TAIL) {  // keys past N: no probability mass, whatever the scales are
+                        if (32 * T + 8 * qd + 4 * g + p >= a.n_tokens - (a.kblocks - 1) * BLK) ev = 0.0f;
+                    }
                     rs += ev;
                     pk = __builtin_amdgcn_cvt_pk_u8_f32(ev, p, pk);  // round-half-even, saturating
                 }

@@ -347,6 +347,30 @@ def test_row_maximum_climbing_hundreds_of_octaves(bits):
         assert st["rel_l2"] < 1e-3
 
 
+@pytest.mark.parametrize("scale", [1e-3, 1e-6])
+@pytest.mark.parametrize("bits_pv", [8, 4])
+def test_padded_keys_get_no_mass_even_when_all_logits_are_tiny(scale, bits_pv):
+    """Inputs of very small magnitude make every logit (and the scale product c) almost zero, so a
+    masked key is excluded only if the kernel excludes it explicitly: on a ragged sequence the padded
+    keys of the last block must still receive no probability."""
+    torch, pb = _torch(), _pb()
+    from paper_2506_16054_amd.pipeline import ParoAttention
+
+    w = SMALL["video64"].replace(nh=2, perm_choice=(3, 0), bits_pv=bits_pv, density=1.0, dtype="f32", seed=81)
+    assert w.N % w.block != 0
+    masks = wl.make_block_masks(w, gather_fn(w))
+    bm, row_ptr, col_idx = blocklist_for(w, masks)
+    q, k, v = wl.make_qkv(w)
+    q, k = (q * np.float32(scale)).astype(np.float32), (k * np.float32(scale)).astype(np.float32)
+    perm_ids = wl.make_perm_ids(w)
+    pa = ParoAttention(pb.shape_of(w), perm_ids, bm, w.bits_qk, bits_pv, torch.float32)
+    o = host(pa.run_fused(*(to_dev(x, "f32") for x in (q, k, v))))
+    torch.cuda.synchronize()
+    for h in range(w.nh):
+        r = oracle_head(w, q[0, h], k[0, h], v[0, h], perm_ids[h], row_ptr[h], col_idx)
+        check_attention(o[0, h], r["o"], po.unpermute(r["flip_risk"], r["idx"]), MAX_ABS, REL_L2, "tiny logits head %d" % h)
+
+
 def test_empty_row_block_gives_zeros():
     torch, pb = _torch(), _pb()
     from paper_2506_16054_amd.pipeline import ParoAttention
