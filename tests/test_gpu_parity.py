@@ -347,7 +347,7 @@ def test_row_maximum_climbing_hundreds_of_octaves(bits):
         assert st["rel_l2"] < 1e-3
 
 
-@pytest.mark.parametrize("scale", [1e-3, 1e-6])
+@pytest.mark.parametrize("scale", [1e-3, 1e-6, 30.0])
 @pytest.mark.parametrize("bits_pv", [8, 4])
 def test_padded_keys_get_no_mass_even_when_all_logits_are_tiny(scale, bits_pv):
     """Inputs of very small magnitude make every logit (and the scale product c) almost zero, so a
