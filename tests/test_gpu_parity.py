@@ -6,7 +6,7 @@ import pytest
 
 from oracle import paro_oracle as po
 from paper_2506_16054_amd import workloads as wl
-from tests.helpers import blocklist_for, check_attention, gather_fn, oracle_head, rel_l2
+from tests.helpers import blocklist_for, check_attention, gather_fn, oracle_head
 
 pytestmark = pytest.mark.gpu
 

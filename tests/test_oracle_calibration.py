@@ -3,7 +3,6 @@ and plain mathematics fix: hand-worked maps, brute-force loops over Eq. (M_spars
 row-stochastic invariants under reordering, closed forms of the combined metric, and a
 constructed head whose best axis order is known."""
 import itertools
-import math
 
 import numpy as np
 import pytest
