@@ -22,8 +22,8 @@
 //
 // Arithmetic per live block (X in log2 units, c = sq_i * sk_j * log2(e) / sqrt(d)):
 //   m' = max(m, c * rowmax S)  (the row maximum is taken on the integers, c > 0);  e = max over valid rows of (c * rowmax S - m')   (<= 0)
-//   E  = qmaxP * 2^(c*S - m' - e)  in (0, qmaxP]  ->  Pc = round-half-even(E) by v_cvt_pk_u8_f32,
-//        which also packs four codes into one register,
+//   E  = qmaxP * 2^(c*S - m' - e)  in (0, qmaxP]  ->  Pc = round-half-even(E), two codes per
+//        v_cvt_pknorm_u16_f32 (E is formed pre-divided by 65535), four codes packed by one v_perm_b32,
 //   l  = l * 2^(m - m') + sP * rowsum(E),  sP = 2^e / qmaxP   (the P tile maximum over qmaxP)
 //   acc = acc * 2^(m - m') + (sP * sv_j) * float(Pc V_j)
 // The two running sums are held divided by 2^(m' - m_ref), m_ref being the row's maximum after its
@@ -382,23 +382,30 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
         // ---- E = qmaxP * 2^(X - m' - e); row sum; round half to even and pack as B operand
         float rs = 0.0f;
         v4i pf[KT];
+        // E is formed divided by 65535, so that v_cvt_pknorm_u16_f32 (which rounds x * 65535 to the
+        // nearest 16-bit integer, two values per instruction) yields the codes; one byte permute
+        // packs four of them.  The row sum carries the same factor, undone in the weight.
+        const float off_n = off - 15.999977986052736f;  // log2(65535)
 #pragma unroll
         for (int T = 0; T < KT; ++T) {
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
-                unsigned pk = 0;
+                float ev[4];
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
-                    float ev = __builtin_amdgcn_exp2f(fmaf(int_result(sacc[T][4 * qd + p]), c, off));
-                    if constexpr (TAIL) {  // keys past N: no probability mass, whatever the scales are
-                        if (32 * T + 8 * qd + 4 * g + p >= a.n_tokens - (a.kblocks - 1) * BLK) ev = 0.0f;
+                    ev[p] = __builtin_amdgcn_exp2f(fmaf(int_result(sacc[T][4 * qd + p]), c, off_n));
+                    if constexpr (TAIL) {
+                        if (32 * T + 8 * qd + 4 * g + p >= a.n_tokens - (a.kblocks - 1) * BLK) ev[p] = 0.0f;
                     }
-                    rs += ev;
-                    pk = __builtin_amdgcn_cvt_pk_u8_f32(ev, p, pk);  // round-half-even, saturating
+                    rs += ev[p];
                 }
-                pf[T][qd] = (int)pk;
+                unsigned lo, hi;
+                asm("v_cvt_pknorm_u16_f32 %0, %1, %2" : "=v"(lo) : "v"(ev[0]), "v"(ev[1]));
+                asm("v_cvt_pknorm_u16_f32 %0, %1, %2" : "=v"(hi) : "v"(ev[2]), "v"(ev[3]));
+                pf[T][qd] = (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u);
             }
         }
+        rs *= 65535.0f;
         l = fmaf(rs, w_blk, l);
 
         // ---- O^T += (sP sv_j 2^(m' - m_ref)) V_j^T P^T
