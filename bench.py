@@ -299,6 +299,17 @@ def main():
         pa.run(q, k, v)
     torch.cuda.synchronize()
     separate_ms = (time.perf_counter() - t2) * 1e3 / min(args.steps, 10)
+    # and the shortest form: Q reordered and quantized inside the attention kernel (three launches)
+    rawq_ms = None
+    if pa.can_fuse_q:
+        for _ in range(10):
+            pa.run_rawq(q, k, v)
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        for i in range(args.steps):
+            pa.run_rawq(q, k, v)
+        torch.cuda.synchronize()
+        rawq_ms = (time.perf_counter() - t3) * 1e3 / args.steps
     attn_ms = sorted(a.elapsed_time(b) for a, b in ev)
     attn_avg = sum(attn_ms) / len(attn_ms)
 
@@ -318,6 +329,7 @@ def main():
         "value": dense_ops / (ms_per_step * 1e-3) / 1e12,
         "unit": "TOPS (4*B*heads*N^2*d / step time; whole path: reorder + quantize + sparse attention + inverse reorder)",
         "separate_steps_ms": separate_ms,
+        "q_quantized_in_attention_ms_per_step": rawq_ms,
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,

@@ -194,6 +194,20 @@ int paro_sparse_attn_unpermuted(const paro_shape* s, int bits_qk, int bits_pv, c
                                 int64_t nnz, const int32_t* row_order, const uint8_t* h_perm_ids,
                                 paro_dtype out_dtype, void* o, void* stream);
 
+/* paro_sparse_attn_unpermuted with the reorder and quantization of Q folded in as well: the
+ * quantization group of Q is the 64-token row block one workgroup owns (Sec. 4.3 (1): groups aligned
+ * with the attention block), so each workgroup gathers its rows of Q by the head's axis order and
+ * quantizes them to 8 bits itself; the Q codes and scales never exist in memory.  Results are
+ * bit-identical to paro_permute_quantize(Q, bits 8) + paro_sparse_attn_unpermuted(bits_qk 8).
+ *   q_dtype  type of q;  q  [B,nh,N,d], default token order, unquantized
+ *   bits_pv  8 or 4;  k, sk, v, sv and everything else as in paro_sparse_attn_unpermuted (bits_qk 8)
+ * Requires block == 64 (PARO_EUNSUPPORTED otherwise). */
+int paro_sparse_attn_unpermuted_rawq(const paro_shape* s, paro_dtype q_dtype, int bits_pv, const void* q,
+                                     const void* k, const float* sk, const void* v, const float* sv,
+                                     const int32_t* row_ptr, const int32_t* col_idx, int64_t nnz,
+                                     const int32_t* row_order, const uint8_t* h_perm_ids,
+                                     paro_dtype out_dtype, void* o, void* stream);
+
 /* ---- mask prefetch (Sec. 4.2 (1) "prefetching sparse masks"; App. C "Overhead of Prefetch") ----
  * Masks differ per transformer block and timestep, so only the mask of the call at hand lives on
  * the GPU: while attention runs with one block list, the caller copies the next bitmask to the

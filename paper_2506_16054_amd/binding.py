@@ -29,7 +29,7 @@ EXPORTS = (
     "paro_perm_index", "paro_vt_slot", "paro_mask_to_blocklist", "paro_permute", "paro_unpermute",
     "paro_quantize", "paro_sparse_attn", "paro_permute_quantize", "paro_sparse_attn_unpermuted", "paro_schedule_rows",
     "paro_mask_to_blocklist_device", "paro_calib_block_stats", "paro_calib_metrics", "paro_calib_choose", "paro_calib_mask",
-    "paro_probe_mfma",
+    "paro_probe_mfma", "paro_sparse_attn_unpermuted_rawq",
 )
 
 
@@ -78,6 +78,7 @@ def lib() -> ctypes.CDLL:
         L.paro_calib_metrics.argtypes = [sp, vp, vp, vp, f32, vp, vp, vp]
         L.paro_calib_choose.argtypes = [i32, vp, vp, f32, vp, vp, vp]
         L.paro_calib_mask.argtypes = [sp, vp, f32, vp, vp]
+        L.paro_sparse_attn_unpermuted_rawq.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i32, vp, vp]
         L.paro_probe_mfma.restype = i64
         L.paro_probe_mfma.argtypes = [i32, i32, vp, i64, vp]
         _lib = L
@@ -353,6 +354,26 @@ def paro_sparse_attn_unpermuted(s: paro_shape, bits_qk: int, bits_pv: int, q, sq
                                              _ptr(sv), _ptr(row_ptr), _ptr(col_idx) if col_idx.numel() else None,
                                              int(col_idx.numel()), _order_ptr(s, row_order), p.ctypes.data, _dtype_code(o), _ptr(o),
                                              _stream()))
+
+
+def paro_sparse_attn_unpermuted_rawq(s: paro_shape, bits_pv: int, q, k, sk, v, sv, row_ptr, col_idx, perm_ids, o, row_order=None) -> None:
+    """q: unquantized [B, nh, N, d] (fp32 or bf16, default order); k, v: 8-bit K codes (rows) and 8/4-bit V codes (transposed)."""
+    import torch
+
+    kb, n = paro_nblocks(s), paro_ntokens(s)
+    _require(q, "q", (s.B, s.nh, n, s.d))
+    _require(k, "k", codes_shape(s, 8, PARO_ROWS), torch.int8)
+    _require(v, "v", codes_shape(s, bits_pv, PARO_VT), torch.int8)
+    for name, t in (("sk", sk), ("sv", sv)):
+        _require(t, name, (s.B, s.nh, kb), torch.float32)
+    _require(row_ptr, "row_ptr", (s.nh, kb + 1), torch.int32)
+    _require(col_idx, "col_idx", None, torch.int32)
+    _require(o, "o", (s.B, s.nh, n, s.d))
+    p = _perm_bytes(s, perm_ids)
+    _check(lib().paro_sparse_attn_unpermuted_rawq(ctypes.byref(s), _dtype_code(q), int(bits_pv), _ptr(q), _ptr(k), _ptr(sk), _ptr(v),
+                                                  _ptr(sv), _ptr(row_ptr), _ptr(col_idx) if col_idx.numel() else None,
+                                                  int(col_idx.numel()), _order_ptr(s, row_order), p.ctypes.data, _dtype_code(o),
+                                                  _ptr(o), _stream()))
 
 
 def paro_sparse_attn(s: paro_shape, bits_qk: int, bits_pv: int, q, sq, k, sk, v, sv, row_ptr, col_idx, op, row_order=None) -> None:

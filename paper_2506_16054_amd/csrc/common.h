@@ -68,6 +68,25 @@ __device__ inline int reorder_dest(const ReorderTable& t, int head, int n) {
     return (q / t.Hg) * mul[0] + (q % t.Hg) * mul[1] + w * mul[2];
 }
 
+// x / scale, correctly rounded, for the many elements of a quantization group that share one divisor
+// (Sec. 4.3 (1): one scale per block).  With y the correctly rounded reciprocal of the divisor,
+// q0 = RN(x y) and r = x - q0 scale (one fma), RN(q0 + r y) is the correctly rounded quotient
+// (Markstein's division theorem).  The theorem excludes divisors whose significand is all ones, and
+// the reciprocal must be a normal number: those groups take the generic divide.  Either way the
+// result equals fl32(x / scale) bit for bit.  Compile with correctly rounded fp32 division.
+struct GroupDivider {
+    float scale, inv;
+    bool generic;
+    __device__ explicit GroupDivider(float s)
+        : scale(s), inv(1.0f / s), generic((__float_as_uint(s) & 0x7fffffu) == 0x7fffffu || !(s > 1e-20f && s < 1e20f)) {}
+    __device__ float operator()(float v) const {
+        if (generic) return v / scale;
+        const float q0 = v * inv;
+        const float rem = fmaf(-q0, scale, v);
+        return fmaf(rem, inv, q0);
+    }
+};
+
 // Slot of token i of a block in the PARO_VT layout: inside every run of 32 tokens the index
 // bits [q1 q0 g p1 p0] are stored as [g q1 q0 p1 p0].  A lane of the 32x32 matrix instruction
 // that produced S^T holds, for one query, the keys 8q + 4g + p (q, p = 0..3) of each 32-key

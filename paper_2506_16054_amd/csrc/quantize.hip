@@ -113,19 +113,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ x
         if (amax > 0.0f) scale = amax / QMAX;  // correctly rounded binary32 divide
     }
     if (tid == 0) scales[group] = scale;
-    // x / scale, correctly rounded, for the many elements that share one divisor: with y the correctly
-    // rounded reciprocal of the divisor, q0 = RN(x y), r = x - q0 scale (one fma), the value
-    // RN(q0 + r y) is the correctly rounded quotient (Markstein's division theorem).  The theorem
-    // excludes divisors whose significand is all ones, and the reciprocal must be a normal number:
-    // those groups take the generic divide.  Either way the code equals rint(fl32(x / scale)).
-    const float inv_scale = 1.0f / scale;
-    const bool generic_divide = (__float_as_uint(scale) & 0x7fffffu) == 0x7fffffu || !(scale > 1e-20f && scale < 1e20f);
-    auto quotient = [&](float v) {
-        if (generic_divide) return v / scale;
-        const float q0 = v * inv_scale;
-        const float rem = fmaf(-q0, scale, v);
-        return fmaf(rem, inv_scale, q0);
-    };
+    const GroupDivider quotient(scale);  // fl32(x / scale) for every element of the group
 
 #pragma unroll
     for (int it = 0; it < IT; ++it) {

@@ -133,8 +133,13 @@ __device__ inline void unpack_nibbles(const v4i x, v4i& first, v4i& second) {
     second = v4i{lo.z, hi.z, lo.w, hi.w};
 }
 
-template <int BLK, int D, int QKBITS, int PVBITS, typename OutT>
+// QSRC selects where this row block's Q operand comes from: 0 = codes and scale written by the
+// quantizer; 1 (bf16) / 2 (fp32) = the unquantized Q tensor in the default token order, in which case
+// the workgroup reorders and quantizes its own 64 x d block on the way in - the quantization group of
+// Q is exactly the row block a workgroup owns (Sec. 4.3 (1)), so no other workgroup needs the result.
+template <int BLK, int D, int QKBITS, int PVBITS, typename OutT, int QSRC = 0>
 __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void attn_i8_kernel(AttnArgs a) {
+    static_assert(QSRC == 0 || QKBITS == 8, "in-kernel quantization of Q produces 8-bit codes");
     constexpr int NW = BLK / 32;
     constexpr int NT = 64 * NW;
     constexpr int KSTR = D + 16;    // padded LDS row strides: rows 16 B apart in bank space
@@ -155,6 +160,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 
     __shared__ __attribute__((aligned(16))) uint8_t lds[2 * STAGE];
     __shared__ unsigned tile_e[2][NW];
+    __shared__ float q_amax[NW];
 
     // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of
     // (head, row block) so the K/V of the heads it works on stay in its own L2.
@@ -185,11 +191,50 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     const uint8_t* vbase = a.v + head_rows * D / VPACK;
     const float* skp = a.sk + (size_t)bh * a.kblocks;
     const float* svp = a.sv + (size_t)bh * a.kblocks;
-    // 4-bit Q and K codes both enter the product times 16
-    const float sq_i = a.sq[(size_t)bh * a.kblocks + i] * a.qk_scale * (QKBITS == 4 ? 1.0f / 256.0f : 1.0f);
-
     v4i qf[KS];
-    if constexpr (QKBITS == 4) {
+    float sq_i = 0.0f;
+    float x[QSRC != 0 ? KS : 1][16];  // this lane's slice of the unquantized row (QSRC != 0)
+    if constexpr (QSRC != 0) {
+        // ---- reorder + quantize this row block of Q here (same arithmetic as the quantizer:
+        // absmax over real rows, scale = absmax / 127 in binary32, code = rint(fl32(x / scale))).
+        // The loads are issued now; the reduction finishes behind the first K/V tile loads.
+        using RawT = std::conditional_t<QSRC == 1, uint16_t, float>;
+        const RawT* qsrc = (const RawT*)a.q + ((size_t)bh * a.n_tokens + (row_valid ? reorder_source(a.table, h, row) : 0)) * D + 16 * g;
+        float amax = 0.0f;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            if (row_valid) {
+                if constexpr (QSRC == 1) {
+                    const uint4 lo = *(const uint4*)(qsrc + 32 * s), hi = *(const uint4*)(qsrc + 32 * s + 8);
+                    const unsigned wv[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        x[s][2 * e] = __uint_as_float(wv[e] << 16);
+                        x[s][2 * e + 1] = __uint_as_float(wv[e] & 0xffff0000u);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float4 f = *(const float4*)(qsrc + 32 * s + 4 * e);
+                        x[s][4 * e] = f.x;
+                        x[s][4 * e + 1] = f.y;
+                        x[s][4 * e + 2] = f.z;
+                        x[s][4 * e + 3] = f.w;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) x[s][e] = 0.0f;
+            }
+#pragma unroll
+            for (int e = 0; e < 16; ++e) amax = fmaxf(amax, fabsf(x[s][e]));
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+        if (lane == 0) q_amax[w] = amax;  // exchanged across the barrier that opens the block loop
+    } else if constexpr (QKBITS == 4) {
+        // 4-bit Q and K codes both enter the product times 16
+        sq_i = a.sq[(size_t)bh * a.kblocks + i] * a.qk_scale * (1.0f / 256.0f);
         const uint8_t* qrow = a.q + ((head_rows + row) * D + 16 * g) / 2;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
@@ -198,6 +243,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
             unpack_nibbles(v4i{(int)x.x, (int)x.y, 0, 0}, qf[s], unused);
         }
     } else {
+        sq_i = a.sq[(size_t)bh * a.kblocks + i] * a.qk_scale;
         const uint8_t* qrow = a.q + (head_rows + row) * D + 16 * g;
 #pragma unroll
         for (int s = 0; s < KS; ++s) qf[s] = *(const v4i*)(qrow + 32 * s);
@@ -296,6 +342,27 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     }
     if (cnt > 1) gload(1);
     __syncthreads();
+    if constexpr (QSRC != 0) {
+        float amax = q_amax[0];
+#pragma unroll
+        for (int ww = 1; ww < NW; ++ww) amax = fmaxf(amax, q_amax[ww]);
+        const float scale = amax > 0.0f ? amax / 127.0f : 1.0f;
+        const GroupDivider quotient(scale);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                unsigned word = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float r = fminf(fmaxf(rintf(quotient(x[s][4 * e4 + e])), -127.0f), 127.0f);
+                    word |= ((unsigned)(int)r & 0xffu) << (8 * e);
+                }
+                qf[s][e4] = (int)word;
+            }
+        }
+        sq_i = scale * a.qk_scale;
+    }
 
     int stage = 0;
     // One live block.  TAIL selects the variant that masks keys past N (only the last column
@@ -710,6 +777,24 @@ static void launch_out(paro_dtype out_dtype, const AttnArgs& a, hipStream_t st) 
         hipLaunchKernelGGL((attn_i8_kernel<BLK, D, QKBITS, PVBITS, uint16_t>), grid, dim3(BLK * 2), 0, st, a);
 }
 
+// Q taken from the unquantized tensor (block 64 only): QSRC 1 = bf16, 2 = fp32
+template <int D, int PVBITS, int QSRC>
+static void launch_rawq(paro_dtype out_dtype, const AttnArgs& a, hipStream_t st) {
+    dim3 grid((unsigned)(a.per_xcd * 8));
+    if (out_dtype == PARO_F32)
+        hipLaunchKernelGGL((attn_i8_kernel<64, D, 8, PVBITS, float, QSRC>), grid, dim3(128), 0, st, a);
+    else
+        hipLaunchKernelGGL((attn_i8_kernel<64, D, 8, PVBITS, uint16_t, QSRC>), grid, dim3(128), 0, st, a);
+}
+
+template <int QSRC>
+static void launch_rawq_shape(int d, int bits_pv, paro_dtype out_dtype, const AttnArgs& a, hipStream_t st) {
+    if (d == 64 && bits_pv == 8) launch_rawq<64, 8, QSRC>(out_dtype, a, st);
+    else if (d == 64) launch_rawq<64, 4, QSRC>(out_dtype, a, st);
+    else if (bits_pv == 8) launch_rawq<128, 8, QSRC>(out_dtype, a, st);
+    else launch_rawq<128, 4, QSRC>(out_dtype, a, st);
+}
+
 template <int QKBITS, int PVBITS>
 static void launch_i8(int blk, int d, paro_dtype out_dtype, const AttnArgs& a, hipStream_t st) {
     if (blk == 64 && d == 64) launch_out<64, 64, QKBITS, PVBITS>(out_dtype, a, st);
@@ -724,9 +809,14 @@ namespace paro {
 static int attn_entry(const char* what, const paro_shape* s, int bits_qk, int bits_pv, const void* q, const float* sq, const void* k,
                       const float* sk, const void* v, const float* sv, const int32_t* row_ptr, const int32_t* col_idx,
                       int64_t nnz, const int32_t* row_order, const uint8_t* h_perm_ids, paro_dtype out_dtype, void* op,
-                      void* stream) {
+                      void* stream, int q_raw = 0) {
     int64_t n, kb;
     if (int st = check_shape(s, &n, &kb)) return st;
+    if (q_raw) {
+        if (bits_qk != 8 || (bits_pv != 8 && bits_pv != 4))
+            return fail(PARO_EUNSUPPORTED, "in-kernel quantization of Q: bits (qk=%d, pv=%d), supported qk 8 with pv 8 or 4", bits_qk, bits_pv);
+        if (s->block != 64) return fail(PARO_EUNSUPPORTED, "in-kernel quantization of Q needs block 64, got %d", s->block);
+    }
     const bool i8 = (bits_qk == 8 || bits_qk == 4) && (bits_pv == 8 || bits_pv == 4);
     const bool b16 = bits_qk == 16 && bits_pv == 16;
     if (!i8 && !b16) {
@@ -736,7 +826,7 @@ static int attn_entry(const char* what, const paro_shape* s, int bits_qk, int bi
     }
     if (out_dtype != PARO_F32 && out_dtype != PARO_BF16) return fail(PARO_EINVAL, "out_dtype=%d is not a paro_dtype", (int)out_dtype);
     if (!q || !k || !v || !op || !row_ptr) return fail(PARO_EINVAL, "q, k, v, op and row_ptr must not be NULL");
-    if (i8 && (!sq || !sk || !sv)) return fail(PARO_EINVAL, "sq, sk and sv are required for integer operands");
+    if (i8 && ((!sq && !q_raw) || !sk || !sv)) return fail(PARO_EINVAL, "sq, sk and sv are required for integer operands");
     if (nnz < 0 || nnz > 0x7fffffffLL) return fail(PARO_EINVAL, "nnz=%lld out of range", (long long)nnz);
     if (nnz > 0 && !col_idx) return fail(PARO_EINVAL, "col_idx is NULL but nnz=%lld", (long long)nnz);
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)op) & 15) return fail(PARO_EINVAL, "q, k, v and op must be 16-byte aligned");
@@ -769,6 +859,9 @@ static int attn_entry(const char* what, const paro_shape* s, int bits_qk, int bi
         const int st = out_dtype == PARO_F32 ? launch_bf16<float>(s->block, s->d, a, (hipStream_t)stream)
                                              : launch_bf16<uint16_t>(s->block, s->d, a, (hipStream_t)stream);
         if (st) return st;
+    } else if (q_raw) {
+        if (q_raw == 1) launch_rawq_shape<1>(s->d, bits_pv, out_dtype, a, (hipStream_t)stream);
+        else launch_rawq_shape<2>(s->d, bits_pv, out_dtype, a, (hipStream_t)stream);
     } else if (bits_qk == 8) {
         if (bits_pv == 8) launch_i8<8, 8>(s->block, s->d, out_dtype, a, (hipStream_t)stream);
         else launch_i8<8, 4>(s->block, s->d, out_dtype, a, (hipStream_t)stream);
@@ -796,4 +889,14 @@ extern "C" int paro_sparse_attn_unpermuted(const paro_shape* s, int bits_qk, int
     if (!h_perm_ids) return paro::fail(PARO_EINVAL, "perm_ids is NULL");
     return paro::attn_entry("paro_sparse_attn_unpermuted", s, bits_qk, bits_pv, q, sq, k, sk, v, sv, row_ptr, col_idx, nnz,
                             row_order, h_perm_ids, out_dtype, o, stream);
+}
+
+extern "C" int paro_sparse_attn_unpermuted_rawq(const paro_shape* s, paro_dtype q_dtype, int bits_pv, const void* q, const void* k,
+                                                const float* sk, const void* v, const float* sv, const int32_t* row_ptr,
+                                                const int32_t* col_idx, int64_t nnz, const int32_t* row_order,
+                                                const uint8_t* h_perm_ids, paro_dtype out_dtype, void* o, void* stream) {
+    if (!h_perm_ids) return paro::fail(PARO_EINVAL, "perm_ids is NULL");
+    if (q_dtype != PARO_F32 && q_dtype != PARO_BF16) return paro::fail(PARO_EINVAL, "q_dtype=%d is not a paro_dtype", (int)q_dtype);
+    return paro::attn_entry("paro_sparse_attn_unpermuted_rawq", s, 8, bits_pv, q, nullptr, k, sk, v, sv, row_ptr, col_idx, nnz, row_order,
+                            h_perm_ids, out_dtype, o, stream, q_dtype == PARO_BF16 ? 1 : 2);
 }

@@ -97,6 +97,27 @@ class ParoAttention:
         self.prepare_fused(q, k, v)
         return self.attend_fused()
 
+    # ---- shortest form (block 64, 8-bit QK): Q is reordered and quantized inside the attention kernel,
+    # by the workgroup that owns the row block; three launches
+    @property
+    def can_fuse_q(self) -> bool:
+        return self.bits_qk == 8 and self.s.block == 64
+
+    def prepare_kv(self, k, v) -> None:
+        _, fk = self._fused_buffers()
+        pb.paro_permute_quantize(self.s, 8, pb.PARO_ROWS, self.perm_ids, k, fk, self.sk)
+        pb.paro_permute_quantize(self.s, self.bits_pv, pb.PARO_VT, self.perm_ids, v, self.vc, self.sv)
+
+    def attend_rawq(self, q):
+        _, fk = self._fused_buffers()
+        pb.paro_sparse_attn_unpermuted_rawq(self.s, self.bits_pv, q, fk, self.sk, self.vc, self.sv, self.row_ptr, self.col_idx,
+                                            self.perm_ids, self.o, self.row_order)
+        return self.o
+
+    def run_rawq(self, q, k, v):
+        self.prepare_kv(k, v)
+        return self.attend_rawq(q)
+
 
 def shared_mask_index(timestep: int, n_timesteps: int) -> int:
     """Which stored mask a sampling step uses under timestep-aware mask sharing (paper Sec. 4.2 (1)):

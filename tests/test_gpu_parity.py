@@ -371,6 +371,47 @@ def test_padded_keys_get_no_mass_even_when_all_logits_are_tiny(scale, bits_pv):
         check_attention(o[0, h], r["o"], po.unpermute(r["flip_risk"], r["idx"]), MAX_ABS, REL_L2, "tiny logits head %d" % h)
 
 
+@pytest.mark.parametrize("name", ["video64", "video64_int4", "flux128"])
+@pytest.mark.parametrize("q_dtype", ["bf16", "f32"])
+def test_in_kernel_q_quantization_is_bit_identical(name, q_dtype):
+    """paro_sparse_attn_unpermuted_rawq (Q reordered and quantized by the workgroup that owns the row
+    block) gives exactly the output of paro_permute_quantize(Q) + paro_sparse_attn_unpermuted, for both
+    input types, on ragged shapes, with text tokens and with 4-bit PV."""
+    torch, pb = _torch(), _pb()
+    from paper_2506_16054_amd.pipeline import ParoAttention
+
+    w = SMALL[name].replace(dtype=q_dtype)
+    s = pb.shape_of(w)
+    perm_ids = wl.make_perm_ids(w)
+    bm = wl.pack_bitmask(wl.make_block_masks(w, gather_fn(w), perm_ids))
+    q, k, v = (to_dev(x, q_dtype) for x in wl.make_qkv(w))
+    q[0, 0, : w.block] *= 1e-30  # a row block of tiny magnitude (generic divide path of the quantizer)
+    pa = ParoAttention(s, perm_ids, bm, 8, w.bits_pv, tdtype(q_dtype))
+    assert pa.can_fuse_q
+    want = pa.run_fused(q, k, v).clone()
+    pa.o.fill_(float("nan"))
+    got = pa.run_rawq(q, k, v)
+    torch.cuda.synchronize()
+    assert not torch.isnan(got).any()
+    assert torch.equal(got, want)
+
+
+def test_in_kernel_q_quantization_rejects_what_it_does_not_cover():
+    torch, pb = _torch(), _pb()
+    from paper_2506_16054_amd.pipeline import ParoAttention
+
+    w = SMALL["video32_f32"]
+    s = pb.shape_of(w)
+    perm_ids = wl.make_perm_ids(w)
+    bm = wl.pack_bitmask(wl.make_block_masks(w, gather_fn(w), perm_ids))
+    pa = ParoAttention(s, perm_ids, bm, 8, 8, torch.float32)
+    assert not pa.can_fuse_q
+    q, k, v = (to_dev(x, "f32") for x in wl.make_qkv(w))
+    with pytest.raises(pb.ParoError) as e:
+        pa.run_rawq(q, k, v)
+    assert e.value.status == pb.PARO_EUNSUPPORTED
+
+
 def test_empty_row_block_gives_zeros():
     torch, pb = _torch(), _pb()
     from paper_2506_16054_amd.pipeline import ParoAttention

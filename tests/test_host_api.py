@@ -116,6 +116,14 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
     assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, *args, -1, None, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
     assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, fake, None, fake, fake, fake, fake, fake, fake, 4, None, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
     assert L.paro_sparse_attn(ctypes.byref(s), 8, 8, *args, 4, None, 5, fake, None) == pb.PARO_EINVAL
+    # attention with in-kernel Q quantization: block 64 and 8-bit QK only
+    b64 = pb.make_shape(1, 2, 64, 2, 8, 8, 0, 64)
+    rq = [fake, fake, fake, fake, fake, fake, fake]
+    assert L.paro_sparse_attn_unpermuted_rawq(ctypes.byref(s), pb.PARO_F32, 8, *rq, 4, None, ok.ctypes.data, pb.PARO_F32, fake, None) == pb.PARO_EUNSUPPORTED
+    assert L.paro_sparse_attn_unpermuted_rawq(ctypes.byref(b64), pb.PARO_F32, 16, *rq, 4, None, ok.ctypes.data, pb.PARO_F32, fake, None) == pb.PARO_EUNSUPPORTED
+    assert L.paro_sparse_attn_unpermuted_rawq(ctypes.byref(b64), 9, 8, *rq, 4, None, ok.ctypes.data, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
+    assert L.paro_sparse_attn_unpermuted_rawq(ctypes.byref(b64), pb.PARO_F32, 8, *rq, 4, None, None, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
+    assert L.paro_sparse_attn_unpermuted_rawq(ctypes.byref(b64), pb.PARO_F32, 8, fake, fake, None, fake, fake, fake, fake, 4, None, ok.ctypes.data, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
     # device-side mask expansion
     assert L.paro_mask_to_blocklist_device(0, 4, fake, fake, fake, 16, None, None) == pb.PARO_EINVAL
     assert L.paro_mask_to_blocklist_device(2, 0, fake, fake, fake, 16, None, None) == pb.PARO_EINVAL
