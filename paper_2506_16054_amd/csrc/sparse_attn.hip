@@ -517,9 +517,12 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 
 // -------------------------------------------------------------------------------------------
 // bf16 unquantized block-sparse mode (the sparse-only rows of the paper's tables): same work
-// split, transposed orientation, LDS ring and block list, on v_mfma_f32_32x32x16_bf16.  P is
-// not quantized, so there is no tile-wide scale and no cross-wavefront exchange; P enters the
-// PV product rounded to bf16 while the denominator accumulates it in fp32.
+// split, transposed orientation and block list, on v_mfma_f32_32x32x16_bf16.  P is not quantized,
+// so there is no tile-wide scale and no cross-wavefront exchange; P enters the PV product rounded
+// to bf16 while the denominator accumulates it in fp32.  The 16-bit tiles are twice as large as
+// the 8-bit ones, so this kernel keeps ONE LDS stage and pays a second barrier per block instead
+// of a second stage: the smaller footprint admits a third wavefront per SIMD (d = 64), which is
+// worth more here than the barrier costs.
 // -------------------------------------------------------------------------------------------
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
@@ -533,11 +536,11 @@ struct Bf16Cfg {
     static constexpr int KBYTES = BLK * KSTR;
     static constexpr int VBYTES = D * VSTR;
     static constexpr int STAGE = KBYTES + VBYTES;
-    static constexpr int LDS_BYTES = 2 * STAGE;
+    static constexpr int LDS_BYTES = STAGE;
 };
 
 template <int BLK, int D, typename OutT>
-__global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
+__global__ __launch_bounds__(BLK * 2, (D == 64 ? 3 : 2)) void attn_bf16_kernel(AttnArgs a) {
     using C = Bf16Cfg<BLK, D>;
     constexpr int NW = BLK / 32;
     constexpr int NT = 64 * NW;
@@ -594,15 +597,6 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
     };
 
     v4i kreg[NKC], vreg[NVC];
-    auto gload = [&](int t) {
-        const int j = col_of(t);
-        const uint8_t* kp = kbase + (size_t)j * (BLK * D * 2);
-        const uint8_t* vp = vbase + (size_t)j * (BLK * D * 2);
-#pragma unroll
-        for (int cc = 0; cc < NKC; ++cc) kreg[cc] = *(const v4i*)(kp + 16 * (tid + NT * cc));
-#pragma unroll
-        for (int cc = 0; cc < NVC; ++cc) vreg[cc] = *(const v4i*)(vp + 16 * (tid + NT * cc));
-    };
     auto lstore_k = [&](int stage) {
         uint8_t* ks = lds + stage * STAGE;
 #pragma unroll
@@ -632,19 +626,30 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[dt][r] = 0.0f;
 
+    // One LDS stage and two barriers per live block: K_t is read before the first barrier; behind it
+    // K_{t+1} and V_t replace K_t and V_{t-1} (every wavefront is past their last reads), the second
+    // barrier publishes them.  Half the LDS footprint, which lets a third wavefront per SIMD in.
+    auto gload_k = [&](int t) {
+        const uint8_t* kp = kbase + (size_t)col_of(t) * (BLK * D * 2);
+#pragma unroll
+        for (int cc = 0; cc < NKC; ++cc) kreg[cc] = *(const v4i*)(kp + 16 * (tid + NT * cc));
+    };
+    auto gload_v = [&](int t) {
+        const uint8_t* vp = vbase + (size_t)col_of(t) * (BLK * D * 2);
+#pragma unroll
+        for (int cc = 0; cc < NVC; ++cc) vreg[cc] = *(const v4i*)(vp + 16 * (tid + NT * cc));
+    };
     if (cnt > 0) {
-        gload(0);
+        gload_k(0);
+        gload_v(0);
         lstore_k(0);
-        lstore_v(0);
+        if (cnt > 1) gload_k(1);
     }
-    if (cnt > 1) gload(1);
     __syncthreads();
 
-    int stage = 0;
+    constexpr int stage = 0;
     auto step = [&](auto tail_tag, int t) {
         constexpr bool TAIL = decltype(tail_tag)::value;
-        const int next = stage ^ 1;
-        if (t + 1 < cnt) lstore_k(next);
         const uint8_t* ks = lds + stage * STAGE;
         const uint8_t* vs = ks + KBYTES;
 
@@ -679,13 +684,15 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
         }
         const float ymax = c * mx;
         __syncthreads();
-        if (t + 1 < cnt) lstore_v(next);
+        lstore_v(0);                      // V_t (loaded one block ago)
+        if (t + 1 < cnt) lstore_k(0);     // K_{t+1}
+        if (t + 1 < cnt) gload_v(t + 1);  // before the column chunk moves on: t+1 may be its last entry
         if (((t + 2) & 63) == 0) {
             cols_cur = cols_nxt;
             ++cur_chunk;
             cols_nxt = load_cols(cur_chunk + 1);
         }
-        if (t + 2 < cnt) gload(t + 2);
+        if (t + 2 < cnt) gload_k(t + 2);
         if (m_ref == -INFINITY) m_ref = ymax;
         if (__builtin_amdgcn_ballot_w64(ymax - m_ref > 64.0f) != 0) {
             const float up = fmaxf(ymax, m_ref);
@@ -716,6 +723,7 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
                 }
         l += rs;
 
+        __syncthreads();  // K_{t+1} and V_t are in place
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -725,7 +733,6 @@ __global__ __launch_bounds__(BLK * 2, 2) void attn_bf16_kernel(AttnArgs a) {
                     const v8bf vf = *(const v8bf*)(vs + (32 * dt + n) * VSTR + 2 * (32 * T + 16 * g + 8 * u));
                     acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[T][u], acc[dt], 0, 0, 0);
                 }
-        stage = next;
     };
 
     const bool has_tail = (a.n_tokens % BLK) != 0 && cnt > 0 && min(max(cols[cnt - 1], 0), a.kblocks - 1) == a.kblocks - 1;
