@@ -218,7 +218,7 @@ def prefetch_overhead(args, w, s, pa, perm_ids, q, k, v):
         "ms_per_step_prefetched": pre,
         "overhead_frac": pre / res - 1.0,
         "load_and_expand_us": e0.elapsed_time(e1) * 1e3,
-        "bytes_per_mask": int(bitmasks[0].size + orders[0].size * 4),
+        "bytes_per_mask": int(pf.h_records.shape[1]),
     }
 
 

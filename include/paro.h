@@ -226,6 +226,16 @@ int paro_sparse_attn_unpermuted_rawq(const paro_shape* s, paro_dtype q_dtype, in
 int paro_mask_to_blocklist_device(int nh, int k, const uint8_t* bitmask, int32_t* row_ptr,
                                   int32_t* col_idx, int64_t cap, int32_t* nnz_out, void* stream);
 
+/* The last step of paro_mask_to_blocklist_device alone, for masks whose offsets were computed
+ * offline (masks are static, Sec. 4.2: `row_ptr` can be stored beside each bitmask, 4 bytes per row
+ * block): writes the live columns of every row block, ascending, at the given offsets.  One small
+ * kernel, so the per-step device work of the mask prefetch is a single copy and a single launch.
+ *   bitmask as above;  row_ptr int32 [nh][k+1] (DEVICE), as paro_mask_to_blocklist produces it;
+ *   col_idx int32 [cap]; entries whose position falls outside [0, cap) are dropped (a corrupt
+ *   row_ptr cannot make the kernel write outside col_idx). */
+int paro_blocklist_cols_device(int nh, int k, const uint8_t* bitmask, const int32_t* row_ptr,
+                               int32_t* col_idx, int64_t cap, void* stream);
+
 /* ---- offline calibration (Sec. 4.1 "Metric for Permutation Order"; Sec. 4.2 (3) "Efficient
  * Offline Mask Generation") -----------------------------------------------------------------
  * Run once per model on one or two calibration samples of Q and K: for each of the six axis

@@ -29,7 +29,7 @@ EXPORTS = (
     "paro_perm_index", "paro_vt_slot", "paro_mask_to_blocklist", "paro_permute", "paro_unpermute",
     "paro_quantize", "paro_sparse_attn", "paro_permute_quantize", "paro_sparse_attn_unpermuted", "paro_schedule_rows",
     "paro_mask_to_blocklist_device", "paro_calib_block_stats", "paro_calib_metrics", "paro_calib_choose", "paro_calib_mask",
-    "paro_probe_mfma", "paro_sparse_attn_unpermuted_rawq",
+    "paro_probe_mfma", "paro_sparse_attn_unpermuted_rawq", "paro_blocklist_cols_device",
 )
 
 
@@ -79,6 +79,7 @@ def lib() -> ctypes.CDLL:
         L.paro_calib_choose.argtypes = [i32, vp, vp, f32, vp, vp, vp]
         L.paro_calib_mask.argtypes = [sp, vp, f32, vp, vp]
         L.paro_sparse_attn_unpermuted_rawq.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i32, vp, vp]
+        L.paro_blocklist_cols_device.argtypes = [i32, i32, vp, vp, vp, i64, vp]
         L.paro_probe_mfma.restype = i64
         L.paro_probe_mfma.argtypes = [i32, i32, vp, i64, vp]
         _lib = L
@@ -265,6 +266,16 @@ def paro_mask_to_blocklist_device(nh: int, k: int, bitmask, row_ptr, col_idx, nn
     cap = 0 if col_idx is None else int(col_idx.numel())
     _check(lib().paro_mask_to_blocklist_device(int(nh), int(k), _ptr(bitmask), _ptr(row_ptr), _ptr(col_idx) if cap else None, cap,
                                                _ptr(nnz_out), _stream()))
+
+
+def paro_blocklist_cols_device(nh: int, k: int, bitmask, row_ptr, col_idx) -> None:
+    """Device tensors: bitmask uint8 [nh, ceil(k*k/8)] and row_ptr int32 [nh, k+1] (precomputed offsets) -> col_idx int32 [cap]."""
+    import torch
+
+    _require(bitmask, "bitmask", (nh, (k * k + 7) // 8), torch.uint8)
+    _require(row_ptr, "row_ptr", (nh, k + 1), torch.int32)
+    _require(col_idx, "col_idx", None, torch.int32)
+    _check(lib().paro_blocklist_cols_device(int(nh), int(k), _ptr(bitmask), _ptr(row_ptr), _ptr(col_idx), int(col_idx.numel()), _stream()))
 
 
 def paro_calib_block_stats(s: paro_shape, q16, k16, eps: float, block_sum, block_max, block_cnt) -> None:

@@ -81,7 +81,7 @@ __global__ __launch_bounds__(256) void blocklist_fill_kernel(int nh, int k, int 
         const bool live = j < k && ((bm[bit >> 3] >> (bit & 7)) & 1);
         const unsigned long long b = __ballot(live);
         const int pos = base + __popcll(b & ((1ull << lane) - 1ull));
-        if (live && pos < cap) col_idx[pos] = j;  // a list that does not fit is truncated, never overrun
+        if (live && (unsigned)pos < (unsigned)cap) col_idx[pos] = j;  // entries outside [0, cap) are dropped, never written
         base += __popcll(b);
     }
 }
@@ -106,4 +106,18 @@ extern "C" int paro_mask_to_blocklist_device(int nh, int k, const uint8_t* bitma
         hipLaunchKernelGGL(blocklist_fill_kernel, dim3((unsigned)((nh * k + 3) / 4)), dim3(256), 0, st, nh, k, nbytes, bitmask, row_ptr,
                            col_idx, (int)cap);
     return check_launch("paro_mask_to_blocklist_device");
+}
+
+extern "C" int paro_blocklist_cols_device(int nh, int k, const uint8_t* bitmask, const int32_t* row_ptr, int32_t* col_idx,
+                                          int64_t cap, void* stream) {
+    using namespace paro;
+    if (nh < 1 || nh > kMaxHeads) return fail(PARO_EINVAL, "nh=%d out of range [1, %d]", nh, kMaxHeads);
+    if (k < 1 || k > 32768) return fail(PARO_EINVAL, "k=%d out of range [1, 32768]", k);
+    if (!bitmask || !row_ptr || !col_idx) return fail(PARO_EINVAL, "bitmask, row_ptr and col_idx must not be NULL");
+    if (cap < 1 || cap > 0x7fffffffLL) return fail(PARO_EINVAL, "cap=%lld out of range", (long long)cap);
+    if ((int64_t)nh * k * k > 0x7fffffffLL) return fail(PARO_EINVAL, "nh*k*k = %lld live blocks cannot be indexed with int32", (long long)nh * k * k);
+    const int nbytes = (int)(((int64_t)k * k + 7) / 8);
+    hipLaunchKernelGGL(blocklist_fill_kernel, dim3((unsigned)((nh * k + 3) / 4)), dim3(256), 0, (hipStream_t)stream, nh, k, nbytes, bitmask,
+                       row_ptr, col_idx, (int)cap);
+    return check_launch("paro_blocklist_cols_device");
 }

@@ -132,10 +132,12 @@ def shared_mask_index(timestep: int, n_timesteps: int) -> int:
 
 class MaskPrefetcher:
     """Two device slots for the block list of the attention call at hand and of the next one
-    (paper Sec. 4.2 (1), App. C "Overhead of Prefetch").  All masks stay in pinned host memory as
-    bitmasks (with the launch order that belongs to each); ``prefetch(slot, t)`` copies mask ``t``
-    to slot ``slot`` on a second stream and expands it there with paro_mask_to_blocklist_device,
-    while the compute stream is busy with the other slot.  Ordering is by events only:
+    (paper Sec. 4.2 (1), App. C "Overhead of Prefetch").  All masks stay in pinned host memory, each as
+    one record [bitmask | row offsets | launch order]: the offsets and the order are functions of the
+    static mask and are computed once, here, when the store is built.  ``prefetch(slot, t)`` copies
+    record ``t`` to slot ``slot`` on a second stream (one transfer, on the copy engine) and writes the
+    column list there with paro_blocklist_cols_device (one small kernel), while the compute stream is
+    busy with the other slot.  Ordering is by events only:
 
         slot.ready   recorded on the copy stream after the expansion; the compute stream waits on
                      it in ``acquire`` before the attention call that reads the slot;
@@ -154,40 +156,54 @@ class MaskPrefetcher:
         if bm.ndim != 3 or bm.shape[1:] != (nh, nbytes):
             raise pb.ParoError(pb.PARO_EINVAL, "h_bitmasks has shape %s, expected (T, %d, %d)" % (bm.shape, nh, nbytes))
         self.T = bm.shape[0]
-        self.h_bitmasks = torch.empty(bm.shape, dtype=torch.uint8, pin_memory=True)
-        self.h_bitmasks.copy_(torch.from_numpy(bm))
-        self.h_row_orders = None
+        n_order = shape.B * nh * k
+        ro = None
         if h_row_orders is not None:
             ro = np.ascontiguousarray(h_row_orders, dtype=np.int32)
-            if ro.shape != (self.T, shape.B * nh * k):
-                raise pb.ParoError(pb.PARO_EINVAL, "h_row_orders has shape %s, expected (%d, %d)" % (ro.shape, self.T, shape.B * nh * k))
-            self.h_row_orders = torch.empty(ro.shape, dtype=torch.int32, pin_memory=True)
-            self.h_row_orders.copy_(torch.from_numpy(ro))
-        self.cap = int(cap) if cap is not None else nh * k * k
+            if ro.shape != (self.T, n_order):
+                raise pb.ParoError(pb.PARO_EINVAL, "h_row_orders has shape %s, expected (%d, %d)" % (ro.shape, self.T, n_order))
+        # record layout, every part 16-byte aligned
+        align = lambda n: (n + 15) // 16 * 16
+        self._off_ptr = align(nh * nbytes)
+        self._off_ord = self._off_ptr + align(nh * (k + 1) * 4)
+        self._rec = self._off_ord + (align(n_order * 4) if ro is not None else 0)
+        host = np.zeros((self.T, self._rec), np.uint8)
+        nnz_max = 1
+        for t in range(self.T):
+            row_ptr, col_idx = pb.paro_mask_to_blocklist(nh, k, bm[t])
+            nnz_max = max(nnz_max, int(col_idx.size))
+            host[t, : nh * nbytes] = bm[t].reshape(-1)
+            host[t, self._off_ptr: self._off_ptr + row_ptr.nbytes] = row_ptr.reshape(-1).view(np.uint8)
+            if ro is not None:
+                host[t, self._off_ord: self._off_ord + ro[t].nbytes] = ro[t].view(np.uint8)
+        self.h_records = torch.empty(host.shape, dtype=torch.uint8, pin_memory=True)
+        self.h_records.copy_(torch.from_numpy(host))
+        self.cap = int(cap) if cap is not None else nnz_max
+        if self.cap < nnz_max:
+            raise pb.ParoError(pb.PARO_EINVAL, "cap=%d is smaller than the longest block list (%d)" % (self.cap, nnz_max))
         self.copy_stream = torch.cuda.Stream(self.dev)
         z = dict(device=self.dev)
         self.slots = []
         for _ in range(2):
+            rec = torch.zeros((self._rec,), dtype=torch.uint8, **z)
             self.slots.append({
-                "bitmask": torch.empty((nh, nbytes), dtype=torch.uint8, **z),
-                "row_ptr": torch.zeros((nh, k + 1), dtype=torch.int32, **z),
+                "record": rec,
+                "bitmask": rec[: nh * nbytes].view(nh, nbytes),
+                "row_ptr": rec[self._off_ptr: self._off_ptr + nh * (k + 1) * 4].view(torch.int32).view(nh, k + 1),
+                "row_order": None if ro is None else rec[self._off_ord: self._off_ord + n_order * 4].view(torch.int32),
                 "col_idx": torch.zeros((self.cap,), dtype=torch.int32, **z),
-                "row_order": None if self.h_row_orders is None else torch.empty((shape.B * nh * k,), dtype=torch.int32, **z),
-                "nnz": torch.zeros((1,), dtype=torch.int32, **z),
                 "ready": torch.cuda.Event(),
                 "free": torch.cuda.Event(),
             })
         torch.cuda.current_stream().synchronize()  # the slots exist before the copy stream touches them
 
     def prefetch(self, slot: int, t: int) -> None:
-        """Enqueue, on the copy stream, the load and expansion of mask ``t`` into ``slot``."""
+        """Enqueue, on the copy stream, the load of record ``t`` into ``slot`` and the expansion of its mask."""
         sl = self.slots[slot]
         with torch.cuda.stream(self.copy_stream):
             self.copy_stream.wait_event(sl["free"])
-            sl["bitmask"].copy_(self.h_bitmasks[t], non_blocking=True)
-            if sl["row_order"] is not None:
-                sl["row_order"].copy_(self.h_row_orders[t], non_blocking=True)
-            pb.paro_mask_to_blocklist_device(self.s.nh, self.k, sl["bitmask"], sl["row_ptr"], sl["col_idx"], sl["nnz"])
+            sl["record"].copy_(self.h_records[t], non_blocking=True)
+            pb.paro_blocklist_cols_device(self.s.nh, self.k, sl["bitmask"], sl["row_ptr"], sl["col_idx"])
             sl["ready"].record(self.copy_stream)
 
     def acquire(self, slot: int):

@@ -68,6 +68,39 @@ def test_device_blocklist_truncates_at_capacity_without_overrun():
     assert nnz0 == ref_cols.size and np.array_equal(row_ptr0, ref_ptr)
 
 
+@pytest.mark.parametrize("nh,k,density", [(1, 1, 1.0), (3, 64, 0.3), (2, 65, 0.5), (48, 275, 0.3)])
+def test_columns_from_precomputed_offsets_equal_oracle(nh, k, density):
+    """paro_blocklist_cols_device: offsets computed offline (here by the oracle), columns written on the device."""
+    torch, pb = _mods()
+    rng = np.random.default_rng([93, nh, k])
+    bits = random_bitmask(rng, nh, k, density, garbage_tail=True)
+    ref_ptr, ref_cols = po.mask_to_blocklist(bits, nh, k)
+    cap = max(int(ref_cols.size), 1)
+    col_idx = torch.full((cap + 16,), -7, dtype=torch.int32, device="cuda:0")
+    pb.paro_blocklist_cols_device(nh, k, torch.from_numpy(bits).to("cuda:0"), torch.from_numpy(ref_ptr).to("cuda:0"), col_idx[:cap])
+    torch.cuda.synchronize()
+    got = col_idx.cpu().numpy()
+    assert np.array_equal(got[: ref_cols.size], ref_cols)
+    assert np.all(got[cap:] == -7)
+
+
+def test_columns_with_corrupt_offsets_stay_inside_the_list():
+    torch, pb = _mods()
+    nh, k = 2, 40
+    rng = np.random.default_rng(94)
+    bits = random_bitmask(rng, nh, k, 0.5)
+    ref_ptr, ref_cols = po.mask_to_blocklist(bits, nh, k)
+    bad = ref_ptr.copy()
+    bad[0, 3] = -1000          # would land before the array
+    bad[1, 7] = 2 ** 30        # would land far behind it
+    cap = int(ref_cols.size)
+    buf = torch.full((cap + 64,), -7, dtype=torch.int32, device="cuda:0")
+    pb.paro_blocklist_cols_device(nh, k, torch.from_numpy(bits).to("cuda:0"), torch.from_numpy(bad).to("cuda:0"), buf[32: 32 + cap])
+    torch.cuda.synchronize()
+    got = buf.cpu().numpy()
+    assert np.all(got[:32] == -7) and np.all(got[32 + cap:] == -7)  # guard zones on both sides untouched
+
+
 def test_prefetched_sequence_is_bit_identical_to_host_built_lists():
     """Five 'timesteps' with different masks through the two slots, two rounds without any host
     synchronisation in between: every output equals the one obtained with that mask's host-built

@@ -131,6 +131,10 @@ def test_device_entry_points_reject_bad_arguments_before_launch():
     assert L.paro_mask_to_blocklist_device(2, 4, fake, fake, None, 16, None, None) == pb.PARO_EINVAL
     assert L.paro_mask_to_blocklist_device(2, 4, fake, fake, fake, -1, None, None) == pb.PARO_EINVAL
     assert L.paro_mask_to_blocklist_device(200, 30000, fake, fake, fake, 16, None, None) == pb.PARO_EINVAL
+    assert L.paro_blocklist_cols_device(2, 4, fake, fake, None, 16, None) == pb.PARO_EINVAL
+    assert L.paro_blocklist_cols_device(2, 4, fake, None, fake, 16, None) == pb.PARO_EINVAL
+    assert L.paro_blocklist_cols_device(2, 4, fake, fake, fake, 0, None) == pb.PARO_EINVAL
+    assert L.paro_blocklist_cols_device(0, 4, fake, fake, fake, 16, None) == pb.PARO_EINVAL
     # offline calibration
     f = ctypes.c_float
     assert L.paro_calib_block_stats(ctypes.byref(s), fake, fake, f(0.0), fake, fake, fake, None) == pb.PARO_EINVAL
