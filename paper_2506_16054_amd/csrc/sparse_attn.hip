@@ -183,6 +183,10 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     const int end = min(max(rp[1], beg), a.nnz);
     const int cnt = end - beg;
     const int* cols = a.col_idx + beg;
+    // A row block that attends more than half of all column blocks (text rows of an image model,
+    // Sec. 4.2 (1)) is on the critical path of the launch: its blocks are visited one after the other,
+    // so its wavefronts get issue priority over the short rows they share a SIMD with.
+    if (2 * cnt > a.kblocks) __builtin_amdgcn_s_setprio(2);
 
     const size_t head_rows = (size_t)bh * a.kblocks * BLK;
     const int row = i * BLK + 32 * w + n;  // this lane's query, in the reordered sequence
