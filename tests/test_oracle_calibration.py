@@ -12,6 +12,26 @@ from oracle import paro_calibration as pc
 from oracle import paro_oracle as po
 
 
+def test_incoherence_of_the_worked_example_and_the_papers_example_thresholds():
+    import json
+    import os
+
+    gold = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_constants.json")))
+    ex = gold["incoherence_example"]
+    x = np.abs(np.array(ex["x"], float))
+    psi = pc.psi_blocks(np.array([[x.max()]]), np.array([[x.sum()]]), np.array([[x.size]]))
+    assert psi[0, 0] == pytest.approx(ex["psi"])
+    # the example thresholds of Sec. 4.1: a block with exactly 90 % of its entries below 1e-3 counts as sparse
+    eps, sigma = gold["sparse_metric_examples"]["epsilon"], gold["sparse_metric_examples"]["sigma"]
+    blk = np.full((10, 10), 2e-3)
+    blk.ravel()[:90] = 5e-4
+    st = pc.block_stats(blk, 10, eps)
+    assert st["cnt"][0, 0] == 90 and pc.m_sparse(st["cnt"], pc.block_entries(10, 10), sigma) == 1.0
+    blk.ravel()[89] = 2e-3
+    st = pc.block_stats(blk, 10, eps)
+    assert st["cnt"][0, 0] == 89 and pc.m_sparse(st["cnt"], pc.block_entries(10, 10), sigma) == 0.0
+
+
 def test_attention_map_is_the_library_softmax_on_bf16_operands():
     rng = np.random.default_rng(1)
     q = rng.standard_normal((37, 16)).astype(np.float32)

@@ -8,7 +8,12 @@ from paper_2506_16054_amd.pipeline import shared_mask_index
 
 def test_timestep_mask_sharing_first_half_distinct_rest_common():
     # paper Sec. 4.2 (1): distinct masks for the first half of the timesteps, one common mask afterwards
-    T = 30  # the sampling schedule the paper uses for CogVideoX
+    import json
+    import os
+
+    gold = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_constants.json")))
+    T = gold["timestep_mask_sharing"]["sampling_steps"]  # the sampling schedule the paper uses for CogVideoX
+    assert T == 30
     idx = [shared_mask_index(t, T) for t in range(T)]
     assert idx[:15] == list(range(15))
     assert set(idx[15:]) == {15}
