@@ -172,7 +172,7 @@ int paro_sparse_attn(const paro_shape* s, int bits_qk, int bits_pv, const void* 
 
 /* ---- fused forms (Sec. 4.1 "Minimize Hardware Overhead"; App. C "Overhead of Permutation") ----
  * The paper removes the cost of the reorder by folding it into neighbouring kernels, so that
- * only read / write-back addresses change.  These two entry points do that at both ends of the
+ * only read / write-back addresses change.  These entry points do that at both ends of the
  * path; results are bit-identical to the unfused calls they replace. */
 
 /* paro_permute followed by paro_quantize without the intermediate tensor: the reorder happens
