@@ -208,7 +208,7 @@ int paro_sparse_attn_unpermuted_rawq(const paro_shape* s, paro_dtype q_dtype, in
                                      const int32_t* row_order, const uint8_t* h_perm_ids,
                                      paro_dtype out_dtype, void* o, void* stream);
 
-/* ---- mask prefetch (Sec. 4.2 (1) "prefetching sparse masks"; App. C "Overhead of Prefetch") ----
+/* ---- mask prefetch (Sec. 4.2 (1), per-head masks fetched just before use; App. C "Overhead of Prefetch") ----
  * Masks differ per transformer block and timestep, so only the mask of the call at hand lives on
  * the GPU: while attention runs with one block list, the caller copies the next bitmask to the
  * device on a second stream and expands it there into a second block list (two buffers, used in

@@ -47,7 +47,7 @@ from typing import Optional, Sequence, Tuple
 import numpy as np
 
 AXES = "FHW"
-# Sec. 4.1: "six possible permutations" of [F, H, W]; numbering is this build's reading.
+# Sec. 4.1: the search space is the 3! = 6 orderings of the axes [F, H, W]; numbering is this build's reading.
 AXIS_ORDERS: Tuple[Tuple[int, int, int], ...] = tuple(itertools.permutations(range(3)))
 
 
