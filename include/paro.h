@@ -109,8 +109,9 @@ int paro_mask_to_blocklist(int nh, int k, const uint8_t* h_bitmask, int32_t* h_r
  * head), so the kernels can start the heaviest row blocks first.  h_order has B*nh*k entries;
  * entry p is the row block (b*nh + h)*k + i that runs at launch position p.  Positions are dealt
  * to the 8 XCDs in 8 contiguous ranges; inside a range, row blocks are sorted by descending live
- * count within groups of consecutive heads whose K and V operands fit one L2 together (so the
- * reordering never evicts the K/V tiles being reused).  bits_* size that footprint.  Host only. */
+ * count within groups of consecutive heads whose K and V operands fit one L2 (4 MB) together (so
+ * the reordering never evicts the K/V tiles being reused); a range whose heads all fit together is
+ * one group.  bits_* size that footprint.  Host only. */
 int paro_schedule_rows(const paro_shape* s, int bits_qk, int bits_pv, const int32_t* h_row_ptr,
                        int32_t* h_order);
 

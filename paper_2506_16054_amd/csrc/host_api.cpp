@@ -170,19 +170,22 @@ int paro_schedule_rows(const paro_shape* s, int bits_qk, int bits_pv, const int3
         return fail(PARO_EINVAL, "bits (qk=%d, pv=%d): expected 4, 8 or 16", bits_qk, bits_pv);
     const int64_t total = (int64_t)s->B * s->nh * k;
     const int64_t per_xcd = (total + 7) / 8;  // the kernels give launch positions [x*per_xcd, (x+1)*per_xcd) to XCD x
-    // Heads whose K and V operands fit one XCD's L2 together are scheduled as one group, so that
-    // starting the heaviest rows first never costs the L2 residency of K/V.
+    // Heads whose K and V operands fit one XCD's L2 (4 MB) together are scheduled as one group, so
+    // that starting the heaviest rows first never costs the L2 residency of K/V.  Groups are
+    // aligned to whole heads; an XCD whose entire range fits the budget is a single group, so a
+    // small problem gets a plain heaviest-first order and no late start of a long row.
     const int64_t kv_bytes = k * s->block * (int64_t)s->d * (bits_qk + bits_pv) / 8;
-    const int64_t l2_budget = 3 << 20;
+    const int64_t l2_budget = 4 << 20;
     const int64_t window = std::max<int64_t>(1, l2_budget / std::max<int64_t>(kv_bytes, 1));
     std::vector<int32_t> ids;
     for (int x = 0; x < 8; ++x) {
         const int64_t lo = x * per_xcd, hi = std::min(total, (x + 1) * per_xcd);
+        const bool one_group = lo < hi && ((hi - 1) / k - lo / k + 1) * kv_bytes <= l2_budget;
         int64_t pos = lo;
         while (pos < hi) {
             const int64_t group = (pos / k) / window;
             int64_t end = pos;
-            while (end < hi && (end / k) / window == group) ++end;
+            while (end < hi && (one_group || (end / k) / window == group)) ++end;
             ids.resize(end - pos);
             for (int64_t t = pos; t < end; ++t) ids[t - pos] = (int32_t)t;
             auto live = [&](int32_t id) {

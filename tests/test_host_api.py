@@ -188,7 +188,8 @@ def test_row_schedule_is_a_permutation_heaviest_first_within_l2_groups():
         for h in np.unique(heads):
             lv = live[h, chunk[heads == h] % k]
             assert np.all(np.diff(lv) <= 0)  # heaviest first
-    # Flux shape: 1.18 MB per head -> two heads per group, sorted together
+    # Flux shape: 1.18 MB per head; an XCD's whole range (three heads, 3.5 MB) fits the L2, so it
+    # is sorted as one group and every long row starts first
     s2 = pb.make_shape(1, 24, 128, 1, 64, 64, 512, 64)
     k2 = 72
     live2 = rng.integers(1, 73, size=(24, k2))
@@ -196,8 +197,30 @@ def test_row_schedule_is_a_permutation_heaviest_first_within_l2_groups():
     rp2[:, 1:] = np.cumsum(live2, axis=1)
     order2 = pb.paro_schedule_rows(s2, 8, 8, rp2)
     assert np.array_equal(np.sort(order2), np.arange(24 * k2))
-    first_group = order2[: 2 * k2]
-    assert set(first_group // k2) == {0, 1}
-    assert np.all(np.diff(live2[first_group // k2, first_group % k2]) <= 0)
+    for x in range(8):
+        chunk = order2[x * 3 * k2:(x + 1) * 3 * k2]
+        assert set(chunk // k2) == {3 * x, 3 * x + 1, 3 * x + 2}
+        assert np.all(np.diff(live2[chunk // k2, chunk % k2]) <= 0)
+    # 20 heads of the same size: XCD ranges of 2.5 heads touch 3 or 4 heads; those touching 3 are
+    # one group, the others fall back to head-aligned groups of three heads
+    s3 = pb.make_shape(1, 20, 128, 1, 64, 64, 512, 64)
+    live3 = rng.integers(1, 73, size=(20, k2))
+    rp3 = np.zeros((20, k2 + 1), np.int32)
+    rp3[:, 1:] = np.cumsum(live3, axis=1)
+    order3 = pb.paro_schedule_rows(s3, 8, 8, rp3)
+    assert np.array_equal(np.sort(order3), np.arange(20 * k2))
+    per3 = 20 * k2 // 8
+    for x in range(8):
+        lo, hi = x * per3, (x + 1) * per3
+        chunk = order3[lo:hi]
+        assert np.array_equal(np.sort(chunk), np.arange(lo, hi))
+        lv = live3[chunk // k2, chunk % k2]
+        if (hi - 1) // k2 - lo // k2 + 1 <= 3:
+            assert np.all(np.diff(lv) <= 0)
+        else:
+            groups = (chunk // k2) // 3
+            assert np.all(np.diff(groups) >= 0)
+            for gidx in np.unique(groups):
+                assert np.all(np.diff(lv[groups == gidx]) <= 0)
     with pytest.raises(pb.ParoError):
         pb.paro_schedule_rows(s2, 5, 8, rp2)
