@@ -5,6 +5,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -33,12 +34,32 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
+def spilling_kernels(remarks: str):
+    """(kernel, bytes per lane) of every kernel whose resource report shows scratch memory."""
+    out, name = [], None
+    for line in remarks.splitlines():
+        m = re.search(r"remark: Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+        m = re.search(r"remark:\s+ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m and int(m.group(1)) > 0:
+            out.append((name, int(m.group(1))))
+    return out
+
+
 def _compile(src: str, extra, objdir: str = LIBDIR) -> str:
     obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
-    cmd = [hipcc(), *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    device = src.endswith(".hip")
+    report = ["-Rpass-analysis=kernel-resource-usage"] if device else []
+    cmd = [hipcc(), *HIPCC_FLAGS, *report, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed on %s:\n%s\n%s" % (src, r.stdout, r.stderr))
+    # Every kernel here is written to live in registers: a spill to scratch memory in a hot loop
+    # costs a multiple of the run time, so it fails the build instead of shipping.
+    spills = spilling_kernels(r.stderr) if device else []
+    if spills and not os.environ.get("PARO_ALLOW_SPILLS"):
+        raise RuntimeError("%s: kernels spill registers to scratch memory: %s" % (src, spills))
     return obj
 
 
