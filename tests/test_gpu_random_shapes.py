@@ -64,3 +64,40 @@ def test_random_shape(i):
         for h in range(w.nh):
             r = oracle_head(w, q[b, h], k[b, h], v[b, h], perm_ids[h], row_ptr[h], col_idx)
             check_attention(got[b, h], r["o"], po.unpermute(r["flip_risk"], r["idx"]), MAX_ABS, rel, "%s b%d h%d" % (w.name, b, h))
+
+
+# Rows with more than 64 and more than 128 live blocks: the kernels fetch the column indices of a
+# row 64 at a time, one chunk ahead, so these lengths cross one and two chunk changes.  Block 32
+# keeps the sequences short enough for the oracle to check every element.
+LONG_ROWS = {
+    "k130_dense_i8": wl.Workload("k130_dense_i8", 1, 1, 64, 2, 8, 259, 0, 32, 1.0, 8, 8, "bf16", 9101),   # N = 4144, ragged
+    "k66_int4pv_d128": wl.Workload("k66_int4pv_d128", 1, 1, 128, 1, 11, 190, 0, 32, 0.9, 8, 4, "f32", 9102),  # N = 2090
+    "k129_bf16": wl.Workload("k129_bf16", 1, 1, 64, 3, 4, 343, 0, 32, 1.0, 16, 16, "f32", 9103),          # N = 4116
+    "k140_i4i4_b64": wl.Workload("k140_i4i4_b64", 1, 1, 64, 2, 7, 638, 0, 64, 0.6, 4, 4, "bf16", 9104),     # N = 8932
+}
+
+
+@pytest.mark.parametrize("name", list(LONG_ROWS))
+def test_long_live_lists(name):
+    import torch
+
+    from paper_2506_16054_amd import binding as pb
+    from paper_2506_16054_amd.pipeline import ParoAttention
+
+    w = LONG_ROWS[name]
+    s = pb.shape_of(w)
+    perm_ids = wl.make_perm_ids(w)
+    masks = wl.make_block_masks(w, gather_fn(w), perm_ids)
+    bm, row_ptr, col_idx = blocklist_for(w, masks)
+    longest = int(np.max(np.diff(row_ptr[0])))
+    assert longest > (128 if w.k > 128 else 64)
+    q, k, v = wl.make_qkv(w)
+    dq, dk, dv = (to_dev(x, w.dtype) for x in (q, k, v))
+    pa = ParoAttention(s, perm_ids, bm, w.bits_qk, w.bits_pv, tdtype(w.dtype))
+    o_fused = pa.run_fused(dq, dk, dv).clone()
+    assert torch.equal(pa.run(dq, dk, dv), o_fused)
+    got = host(o_fused)
+    r = oracle_head(w, q[0, 0], k[0, 0], v[0, 0], perm_ids[0], row_ptr[0], col_idx)
+    rel = REL_L2_BF16 if w.bits_qk == 16 else REL_L2
+    st = check_attention(got[0, 0], r["o"], po.unpermute(r["flip_risk"], r["idx"]), MAX_ABS, rel, name)
+    print("%s: N %d, longest row %d blocks, max_abs %.2e rel_l2 %.2e" % (name, w.N, longest, st["max_abs"], st["rel_l2"]))
