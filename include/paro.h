@@ -185,6 +185,17 @@ int paro_permute_quantize(const paro_shape* s, paro_dtype dtype, int bits, paro_
                           const uint8_t* h_perm_ids, const void* x, void* codes, float* scales,
                           void* stream);
 
+/* The three paro_permute_quantize calls of one attention call in a single launch: Q and K become
+ * PARO_ROWS codes of bits_qk, V becomes PARO_VT codes of bits_pv, each bit-identical to the separate
+ * call.  (bits_qk, bits_pv) is one of (8,8), (8,4), (4,4), (4,8), (16,16).
+ *   q, k, v     [B,nh,N,d] dtype, default token order
+ *   *_codes, s* as paro_quantize lays them out for the given bits and layout; none may alias an input
+ *               or another output */
+int paro_permute_quantize_qkv(const paro_shape* s, paro_dtype dtype, int bits_qk, int bits_pv,
+                              const uint8_t* h_perm_ids, const void* q, const void* k, const void* v,
+                              void* q_codes, float* sq, void* k_codes, float* sk, void* v_codes, float* sv,
+                              void* stream);
+
 /* paro_sparse_attn followed by paro_unpermute without the intermediate tensor: row n' of the
  * result is stored at row idx_h[n'] of o.  Arguments as paro_sparse_attn, plus
  *   h_perm_ids  host, [nh], values 0..5

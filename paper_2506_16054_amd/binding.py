@@ -29,7 +29,7 @@ EXPORTS = (
     "paro_perm_index", "paro_vt_slot", "paro_mask_to_blocklist", "paro_permute", "paro_unpermute",
     "paro_quantize", "paro_sparse_attn", "paro_permute_quantize", "paro_sparse_attn_unpermuted", "paro_schedule_rows",
     "paro_mask_to_blocklist_device", "paro_calib_block_stats", "paro_calib_metrics", "paro_calib_choose", "paro_calib_mask",
-    "paro_probe_mfma", "paro_sparse_attn_unpermuted_rawq", "paro_blocklist_cols_device",
+    "paro_probe_mfma", "paro_sparse_attn_unpermuted_rawq", "paro_blocklist_cols_device", "paro_permute_quantize_qkv",
 )
 
 
@@ -80,6 +80,7 @@ def lib() -> ctypes.CDLL:
         L.paro_calib_mask.argtypes = [sp, vp, f32, vp, vp]
         L.paro_sparse_attn_unpermuted_rawq.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i32, vp, vp]
         L.paro_blocklist_cols_device.argtypes = [i32, i32, vp, vp, vp, i64, vp]
+        L.paro_permute_quantize_qkv.argtypes = [sp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.paro_probe_mfma.restype = i64
         L.paro_probe_mfma.argtypes = [i32, i32, vp, i64, vp]
         _lib = L
@@ -250,6 +251,22 @@ def paro_permute_quantize(s: paro_shape, bits: int, layout: int, perm_ids, x, co
     p = _perm_bytes(s, perm_ids)
     _check(lib().paro_permute_quantize(ctypes.byref(s), _dtype_code(x), int(bits), int(layout), p.ctypes.data, _ptr(x), _ptr(codes),
                                        _ptr(scales), _stream()))
+
+
+def paro_permute_quantize_qkv(s: paro_shape, bits_qk: int, bits_pv: int, perm_ids, q, k, v, q_codes, sq, k_codes, sk, v_codes, sv) -> None:
+    import torch
+
+    for name, x in (("q", q), ("k", k), ("v", v)):
+        _require(x, name, (s.B, s.nh, paro_ntokens(s), s.d), q.dtype)
+    ct_qk = torch.bfloat16 if bits_qk == 16 else torch.int8
+    _require(q_codes, "q_codes", codes_shape(s, bits_qk, PARO_ROWS), ct_qk)
+    _require(k_codes, "k_codes", codes_shape(s, bits_qk, PARO_ROWS), ct_qk)
+    _require(v_codes, "v_codes", codes_shape(s, bits_pv, PARO_VT), torch.bfloat16 if bits_pv == 16 else torch.int8)
+    for name, x in (("sq", sq), ("sk", sk), ("sv", sv)):
+        _require(x, name, (s.B, s.nh, paro_nblocks(s)), torch.float32)
+    p = _perm_bytes(s, perm_ids)
+    _check(lib().paro_permute_quantize_qkv(ctypes.byref(s), _dtype_code(q), int(bits_qk), int(bits_pv), p.ctypes.data, _ptr(q), _ptr(k),
+                                           _ptr(v), _ptr(q_codes), _ptr(sq), _ptr(k_codes), _ptr(sk), _ptr(v_codes), _ptr(sv), _stream()))
 
 
 def paro_mask_to_blocklist_device(nh: int, k: int, bitmask, row_ptr, col_idx, nnz_out=None) -> None:

@@ -52,9 +52,8 @@ __device__ inline float wave_max(float v) {
 //                 Sec. 4.1 happens on the way in (row n' of the group reads row idx(n') of x), so
 //                 the reordered tensor never exists in memory.
 template <typename InT, int BLK, int D, int BITS, int LAYOUT, bool GATHER>
-__global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ xp, uint8_t* __restrict__ codes,
-                                                       float* __restrict__ scales, int n_tokens, int kblocks,
-                                                       ReorderTable table, int nh) {
+__device__ __forceinline__ void quantize_group(const InT* __restrict__ xp, uint8_t* __restrict__ codes, float* __restrict__ scales,
+                                               int n_tokens, int kblocks, const ReorderTable& table, int nh, int blk, int bh) {
     constexpr int ELEMS = BLK * D;
     constexpr int CHUNKS = ELEMS / 8;  // 8 consecutive channels of one token per chunk
     constexpr int IT = (CHUNKS + 255) / 256;
@@ -69,8 +68,6 @@ __global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ x
     __shared__ __attribute__((aligned(16))) uint8_t stage[STAGE_BYTES];
     __shared__ float wave_amax[4];
 
-    const int blk = blockIdx.x;
-    const int bh = blockIdx.y;
     const int tid = threadIdx.x;
     const size_t group = (size_t)bh * kblocks + blk;
     const InT* tile = GATHER ? xp + (size_t)bh * n_tokens * D : xp + group * ELEMS;
@@ -183,6 +180,33 @@ __global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ x
     }
 }
 
+template <typename InT, int BLK, int D, int BITS, int LAYOUT, bool GATHER>
+__global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ xp, uint8_t* __restrict__ codes,
+                                                       float* __restrict__ scales, int n_tokens, int kblocks,
+                                                       ReorderTable table, int nh) {
+    quantize_group<InT, BLK, D, BITS, LAYOUT, GATHER>(xp, codes, scales, n_tokens, kblocks, table, nh, blockIdx.x, blockIdx.y);
+}
+
+// Q, K and V of one attention call in a single launch (blockIdx.z selects the tensor): Q and K as
+// row-major codes of QKBITS, V as transposed blocks of PVBITS, all three reordered on the way in.
+// Same arithmetic as three quantize_kernel launches, two launch gaps fewer.
+struct QkvPointers {
+    const void* in[3];
+    uint8_t* codes[3];
+    float* scales[3];
+};
+
+template <typename InT, int BLK, int D, int QKBITS, int PVBITS>
+__global__ __launch_bounds__(256) void quantize_qkv_kernel(QkvPointers p, int n_tokens, int kblocks, ReorderTable table, int nh) {
+    const int z = blockIdx.z;
+    if (z < 2)
+        quantize_group<InT, BLK, D, QKBITS, PARO_ROWS, true>((const InT*)p.in[z], p.codes[z], p.scales[z], n_tokens, kblocks, table, nh,
+                                                             blockIdx.x, blockIdx.y);
+    else
+        quantize_group<InT, BLK, D, PVBITS, PARO_VT, true>((const InT*)p.in[2], p.codes[2], p.scales[2], n_tokens, kblocks, table, nh,
+                                                           blockIdx.x, blockIdx.y);
+}
+
 struct QuantLaunch {
     dim3 grid;
     hipStream_t stream;
@@ -255,7 +279,63 @@ static int quantize_entry(const char* what, const paro_shape* s, paro_dtype dtyp
     return check_launch(what);
 }
 
+template <typename InT, int BLK, int D>
+static bool launch_qkv_bits(int bits_qk, int bits_pv, dim3 grid, hipStream_t st, const QkvPointers& p, int n, int k, const ReorderTable& t, int nh) {
+#define PARO_QKV_CASE(QK, PV)                                                                                              \
+    if (bits_qk == QK && bits_pv == PV) {                                                                                  \
+        hipLaunchKernelGGL((quantize_qkv_kernel<InT, BLK, D, QK, PV>), grid, dim3(256), 0, st, p, n, k, t, nh);            \
+        return true;                                                                                                       \
+    }
+    PARO_QKV_CASE(8, 8)
+    PARO_QKV_CASE(8, 4)
+    PARO_QKV_CASE(4, 4)
+    PARO_QKV_CASE(4, 8)
+    PARO_QKV_CASE(16, 16)
+#undef PARO_QKV_CASE
+    return false;
+}
+
+template <typename InT>
+static bool launch_qkv_shape(int blk, int d, int bits_qk, int bits_pv, dim3 grid, hipStream_t st, const QkvPointers& p, int n, int k,
+                             const ReorderTable& t, int nh) {
+    if (blk == 64 && d == 64) return launch_qkv_bits<InT, 64, 64>(bits_qk, bits_pv, grid, st, p, n, k, t, nh);
+    if (blk == 64 && d == 128) return launch_qkv_bits<InT, 64, 128>(bits_qk, bits_pv, grid, st, p, n, k, t, nh);
+    if (blk == 32 && d == 64) return launch_qkv_bits<InT, 32, 64>(bits_qk, bits_pv, grid, st, p, n, k, t, nh);
+    return launch_qkv_bits<InT, 32, 128>(bits_qk, bits_pv, grid, st, p, n, k, t, nh);
+}
+
 }  // namespace paro
+
+extern "C" int paro_permute_quantize_qkv(const paro_shape* s, paro_dtype dtype, int bits_qk, int bits_pv, const uint8_t* h_perm_ids,
+                                         const void* q, const void* k, const void* v, void* q_codes, float* sq, void* k_codes,
+                                         float* sk, void* v_codes, float* sv, void* stream) {
+    using namespace paro;
+    int64_t n, kb;
+    if (int st = check_shape(s, &n, &kb)) return st;
+    if (dtype != PARO_F32 && dtype != PARO_BF16) return fail(PARO_EINVAL, "dtype=%d is not a paro_dtype", (int)dtype);
+    if (!h_perm_ids) return fail(PARO_EINVAL, "perm_ids is NULL");
+    if (!q || !k || !v || !q_codes || !k_codes || !v_codes || !sq || !sk || !sv)
+        return fail(PARO_EINVAL, "inputs, codes and scales must not be NULL");
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)q_codes | (uintptr_t)k_codes | (uintptr_t)v_codes) & 15)
+        return fail(PARO_EINVAL, "inputs and codes must be 16-byte aligned");
+    const void* ins[3] = {q, k, v};
+    const void* outs[3] = {q_codes, k_codes, v_codes};
+    for (int a = 0; a < 3; ++a)
+        for (int b = 0; b < 3; ++b)
+            if (ins[a] == outs[b] || (a < b && outs[a] == outs[b])) return fail(PARO_EINVAL, "inputs and codes must not alias");
+    QkvPointers p;
+    for (int a = 0; a < 3; ++a) p.in[a] = ins[a];
+    p.codes[0] = (uint8_t*)q_codes; p.codes[1] = (uint8_t*)k_codes; p.codes[2] = (uint8_t*)v_codes;
+    p.scales[0] = sq; p.scales[1] = sk; p.scales[2] = sv;
+    ReorderTable table;
+    if (int st = make_reorder_table(s, h_perm_ids, &table)) return st;
+    const dim3 grid((unsigned)kb, (unsigned)(s->B * s->nh), 3);
+    const bool ok = dtype == PARO_F32
+        ? launch_qkv_shape<float>(s->block, s->d, bits_qk, bits_pv, grid, (hipStream_t)stream, p, (int)n, (int)kb, table, s->nh)
+        : launch_qkv_shape<uint16_t>(s->block, s->d, bits_qk, bits_pv, grid, (hipStream_t)stream, p, (int)n, (int)kb, table, s->nh);
+    if (!ok) return fail(PARO_EINVAL, "bits (qk=%d, pv=%d): expected (8,8), (8,4), (4,4), (4,8) or (16,16)", bits_qk, bits_pv);
+    return check_launch("paro_permute_quantize_qkv");
+}
 
 extern "C" int paro_quantize(const paro_shape* s, paro_dtype dtype, int bits, paro_layout layout, const void* xp,
                              void* codes, float* scales, void* stream) {

@@ -87,6 +87,11 @@ class ParoAttention:
         pb.paro_permute_quantize(s, self.bits_qk, pb.PARO_ROWS, self.perm_ids, k, fk, self.sk)
         pb.paro_permute_quantize(s, self.bits_pv, pb.PARO_VT, self.perm_ids, v, self.vc, self.sv)
 
+    def prepare_fused_qkv(self, q, k, v) -> None:
+        """prepare_fused in one launch (Q, K and V quantized by one grid)."""
+        fq, fk = self._fused_buffers()
+        pb.paro_permute_quantize_qkv(self.s, self.bits_qk, self.bits_pv, self.perm_ids, q, k, v, fq, self.sq, fk, self.sk, self.vc, self.sv)
+
     def attend_fused(self):
         fq, fk = self._fused_buffers()
         pb.paro_sparse_attn_unpermuted(self.s, self.bits_qk, self.bits_pv, fq, self.sq, fk, self.sk, self.vc, self.sv,

@@ -457,6 +457,21 @@ def test_fused_entry_points_are_bit_identical_to_the_separate_steps(name):
         for got, ref in zip((pa.sq, pa.sk, pa.sv), ref_s):
             assert torch.equal(got, ref)
     assert torch.equal(o, ref_o)
+    # the three quantizer launches as one
+    fq.fill_(1)
+    fk.fill_(1)
+    pa.vc.fill_(1)
+    for t in (pa.sq, pa.sk, pa.sv):
+        t.fill_(float("nan"))
+    pa.prepare_fused_qkv(p.dq, p.dk, p.dv)
+    torch.cuda.synchronize()
+    assert torch.equal(fq.view(torch.uint8) if fq.dtype == torch.int8 else fq, ref_q.view(torch.uint8) if ref_q.dtype == torch.int8 else ref_q)
+    assert torch.equal(fk.view(torch.uint8) if fk.dtype == torch.int8 else fk, ref_k.view(torch.uint8) if ref_k.dtype == torch.int8 else ref_k)
+    assert torch.equal(pa.vc, ref_v)
+    for got, ref in zip((pa.sq, pa.sk, pa.sv), ref_s):
+        assert torch.equal(got, ref) or p.w.bits_qk == 16
+    if p.w.bits_qk == 16:
+        assert all(bool((t == 1).all()) for t in (pa.sq, pa.sk, pa.sv))
 
 
 @pytest.mark.parametrize("name", ["video64", "flux128", "video64_bf16"])

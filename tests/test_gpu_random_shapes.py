@@ -54,6 +54,8 @@ def test_random_shape(i):
     assert torch.equal(o_sep, o_fused), "fused entry points differ from the separate steps"
     if pa.can_fuse_q:
         assert torch.equal(pa.run_rawq(dq, dk, dv), o_fused), "in-kernel Q quantization differs"
+    pa.prepare_fused_qkv(dq, dk, dv)
+    assert torch.equal(pa.attend_fused(), o_fused), "the one-launch quantizer differs from the three calls"
     saved = pa.row_order
     pa.row_order = None
     assert torch.equal(pa.run_fused(dq, dk, dv), o_fused), "the launch order changed the result"

@@ -162,6 +162,21 @@ def test_fused_entry_points_validate_on_the_host():
     assert L.paro_permute_quantize(ctypes.byref(s), pb.PARO_F32, 8, pb.PARO_ROWS, None, fake, ctypes.c_void_p(0x2000), fake, None) == pb.PARO_EINVAL
     assert L.paro_permute_quantize(ctypes.byref(s), pb.PARO_F32, 8, pb.PARO_ROWS, bad.ctypes.data, fake, ctypes.c_void_p(0x2000), fake, None) == pb.PARO_EINVAL
     assert L.paro_permute_quantize(ctypes.byref(s), pb.PARO_F32, 3, pb.PARO_ROWS, ok.ctypes.data, fake, ctypes.c_void_p(0x2000), fake, None) == pb.PARO_EINVAL
+    # the one-launch form of the three quantizer calls
+    ptr = lambda a: ctypes.c_void_p(a)
+    ins = [ptr(0x1000), ptr(0x2000), ptr(0x3000)]
+    outs = [ptr(0x4000), fake, ptr(0x5000), fake, ptr(0x6000), fake]  # codes, scales alternating
+    qkv = lambda bits_qk, bits_pv, perm, i, o, dt=pb.PARO_F32: L.paro_permute_quantize_qkv(ctypes.byref(s), dt, bits_qk, bits_pv, perm, *i, *o, None)
+    assert qkv(8, 8, None, ins, outs) == pb.PARO_EINVAL                       # no perm_ids
+    assert qkv(8, 8, bad.ctypes.data, ins, outs) == pb.PARO_EINVAL            # perm id out of range
+    assert qkv(8, 16, ok.ctypes.data, ins, outs) == pb.PARO_EINVAL            # unsupported pair of widths
+    assert qkv(3, 8, ok.ctypes.data, ins, outs) == pb.PARO_EINVAL
+    assert qkv(8, 8, ok.ctypes.data, ins, outs, 7) == pb.PARO_EINVAL          # dtype
+    assert qkv(8, 8, ok.ctypes.data, [ptr(0x1000), None, ptr(0x3000)], outs) == pb.PARO_EINVAL
+    assert qkv(8, 8, ok.ctypes.data, [ptr(0x1004), ptr(0x2000), ptr(0x3000)], outs) == pb.PARO_EINVAL  # alignment
+    assert qkv(8, 8, ok.ctypes.data, ins, [ptr(0x1000), fake, ptr(0x5000), fake, ptr(0x6000), fake]) == pb.PARO_EINVAL  # output aliases an input
+    assert qkv(8, 8, ok.ctypes.data, ins, [ptr(0x4000), fake, ptr(0x4000), fake, ptr(0x6000), fake]) == pb.PARO_EINVAL  # two outputs alias
+    assert b"alias" in L.paro_last_error()
     args = [fake] * 8
     assert L.paro_sparse_attn_unpermuted(ctypes.byref(s), 8, 8, *args, 4, None, None, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
     assert L.paro_sparse_attn_unpermuted(ctypes.byref(s), 8, 8, *args, 4, None, bad.ctypes.data, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
