@@ -96,18 +96,18 @@ __device__ inline int xor32_max(int x) {
     return max((int)r[0], (int)r[1]);
 }
 
-// Minimum over the wavefront of unsigned values, as a wave-uniform value.  Rows of 16 lanes are
-// reduced with DPP (xor 1, xor 2, half mirror, mirror); the four row results are combined
-// through scalar registers.  Used on the bit patterns of floats that are all <= 0 (or -inf):
-// for those a larger value has the smaller bit pattern, so this is their maximum.
+// Minimum over the wavefront of unsigned values that are equal in lanes l and l + 32 (the two
+// lanes of a query), as a wave-uniform value.  Rows of 16 lanes are reduced with DPP (xor 1, xor 2,
+// half mirror, mirror); rows 0 and 1 then cover the wave and are combined through scalar registers.
+// Used on the bit patterns of floats that are all <= 0 (or -inf): for those a larger value has the
+// smaller bit pattern, so this is their maximum.
 __device__ inline unsigned wave_umin(unsigned x) {
     x = min(x, (unsigned)dpp_mov<0xB1>((int)x));   // quad_perm [1,0,3,2]
     x = min(x, (unsigned)dpp_mov<0x4E>((int)x));   // quad_perm [2,3,0,1]
     x = min(x, (unsigned)dpp_mov<0x141>((int)x));  // row_half_mirror
     x = min(x, (unsigned)dpp_mov<0x140>((int)x));  // row_mirror
     const unsigned r0 = __builtin_amdgcn_readlane(x, 0), r1 = __builtin_amdgcn_readlane(x, 16);
-    const unsigned r2 = __builtin_amdgcn_readlane(x, 32), r3 = __builtin_amdgcn_readlane(x, 48);
-    return min(min(r0, r1), min(r2, r3));
+    return min(r0, r1);
 }
 
 // Integer matrix results become floats without a convert instruction: every accumulator chain
@@ -278,46 +278,48 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 #pragma unroll
         for (int c = 0; c < NVC; ++c) vreg[c] = *(const v4i*)(vp + 16 * (tid + NT * c));
     };
+    // LDS store offsets of this thread's 16-byte pieces: piece c lies a whole number of rows below
+    // piece 0, so one address per tile and stage serves all pieces through immediate offsets.
+    constexpr int KROWB = D / KPACK, VROWB = BLK / VPACK;  // bytes of one stored row in global memory
+    static_assert((16 * NT) % KROWB == 0 && (16 * NT) % VROWB == 0, "pieces must be whole rows apart");
+    const int k_off = ((16 * tid) / KROWB) * KSTR + KPACK * ((16 * tid) % KROWB);
+    const int v_off = KBYTES + ((16 * tid) / VROWB) * VSTR + VPACK * ((16 * tid) % VROWB);
     auto lstore_k = [&](int stage) {
-        uint8_t* ks = lds + stage * STAGE;
+        uint8_t* dst0 = lds + stage * STAGE + k_off;
 #pragma unroll
         for (int c = 0; c < NKC; ++c) {
-            const int o = 16 * (tid + NT * c);
+            uint8_t* dst = dst0 + c * (16 * NT / KROWB) * KSTR;
             if constexpr (QKBITS == 4) {  // 16 packed bytes = 32 channels of one key
-                constexpr int PROW = D / 2;
                 v4i first, second;
                 unpack_nibbles(kreg[c], first, second);
-                uint8_t* dst = ks + (o / PROW) * KSTR + 2 * (o % PROW);
                 *(v4i*)dst = first;
                 *(v4i*)(dst + 16) = second;
             } else {
-                *(v4i*)(ks + (o / D) * KSTR + (o % D)) = kreg[c];
+                *(v4i*)dst = kreg[c];
             }
         }
     };
     auto lstore_v = [&](int stage) {
-        uint8_t* vs = lds + stage * STAGE + KBYTES;
+        uint8_t* dst0 = lds + stage * STAGE + v_off;
 #pragma unroll
         for (int c = 0; c < NVC; ++c) {
-            const int o = 16 * (tid + NT * c);
+            uint8_t* dst = dst0 + c * (16 * NT / VROWB) * VSTR;
             if constexpr (PVBITS == 4) {
                 // 16 packed bytes = 32 slots of one channel (the PARO_VT nibble order makes the
                 // unpacked bytes land in slot order)
-                constexpr int PROW = BLK / 2;
                 v4i first, second;
                 unpack_nibbles(vreg[c], first, second);
-                uint8_t* dst = vs + (o / PROW) * VSTR + 2 * (o % PROW);
                 *(v4i*)dst = first;
                 *(v4i*)(dst + 16) = second;
             } else {
-                *(v4i*)(vs + (o / BLK) * VSTR + (o % BLK)) = vreg[c];
+                *(v4i*)dst = vreg[c];
             }
         }
     };
 
     float m = -INFINITY;  // running row maximum, log2 units
-    float m_ref = 0.0f;   // the maximum the stored sums are expressed against
-    float l = 0.0f;       // this lane's share of the running denominator (divided by 2^(m - m_ref))
+    float m_ref = -INFINITY;  // the maximum the stored sums are expressed against (set by the first block)
+    float l = 0.0f;       // this lane's share of the running denominator, divided by 65535 * 2^(m - m_ref)
     float acc[DT][16];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -410,7 +412,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
         for (int T = 0; T < KT; ++T)
 #pragma unroll
             for (int r = 0; r < 16; ++r) part[r & 3] = max(part[r & 3], sacc[T][r]);
-        const float ymax = c * (float)(xor32_max(max(max(part[0], part[1]), max(part[2], part[3]))) - kAccBiasI);
+        const float ymax = c * int_result(xor32_max(max(max(part[0], part[1]), max(part[2], part[3]))));
         const float m_new = fmaxf(m, ymax);
         // e = log2 of the largest entry of the Pt tile = max over valid rows of (row maximum of
         // the block - running maximum), always <= 0; reduced as an unsigned minimum of bit patterns
@@ -432,7 +434,8 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
             for (int ww = 0; ww < NW; ++ww) eb = min(eb, tile_e[t & 1][ww]);
         }
         const float e = __uint_as_float(eb);
-        if (m == -INFINITY) m_ref = m_new;  // first block of the row: its maximum becomes the reference
+        // The first block of a row finds m_ref = -inf: growth = +inf takes the branch below, which
+        // scales the (zero) sums by 2^-inf = 0 and makes the block's maximum the reference.
         float growth = m_new - m_ref;
         if (__builtin_amdgcn_ballot_w64(growth > 64.0f) != 0) {  // keep the stored sums far from overflow
             const float down = __builtin_amdgcn_exp2f(-growth);
@@ -445,7 +448,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
             growth = 0.0f;
         }
         // weight of this block's terms in the stored sums: sP * 2^(m' - m_ref)
-        const float w_blk = __builtin_amdgcn_exp2f(e + growth) * (1.0f / QMAXP);
+        const float w_blk = __builtin_amdgcn_exp2f(e + growth - LOG2_QMAXP);
         // exponent offset: X - m' - e + log2(qmaxP), so that the tile maximum maps to qmaxP
         const float off = LOG2_QMAXP - m_new - e;
         m = m_new;
@@ -468,16 +471,17 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
                     if constexpr (TAIL) {
                         if (32 * T + 8 * qd + 4 * g + p >= a.n_tokens - (a.kblocks - 1) * BLK) ev[p] = 0.0f;
                     }
-                    rs += ev[p];
+                    rs = (T == 0 && qd == 0 && p == 0) ? ev[p] : rs + ev[p];
                 }
-                unsigned lo, hi;
-                asm("v_cvt_pknorm_u16_f32 %0, %1, %2" : "=v"(lo) : "v"(ev[0]), "v"(ev[1]));
-                asm("v_cvt_pknorm_u16_f32 %0, %1, %2" : "=v"(hi) : "v"(ev[2]), "v"(ev[3]));
+                // (the builtin, not inline assembly: the instruction consumes results of the
+                // transcendental unit, and only instructions the compiler can see get the wait state
+                // that this needs when they follow the exponential directly)
+                const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[0], ev[1]));
+                const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[2], ev[3]));
                 pf[T][qd] = (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u);
             }
         }
-        rs *= 65535.0f;
-        l = fmaf(rs, w_blk, l);
+        l = fmaf(rs, w_blk, l);  // rs carries the factor 1/65535; it is undone once, at the end
 
         // ---- O^T += (sP sv_j 2^(m' - m_ref)) V_j^T P^T
         const float sv_eff = w_blk * sv_cur * (PVBITS == 4 ? 0.0625f : 1.0f);
@@ -505,7 +509,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     if (has_tail) step(std::true_type{}, cnt - 1);
 
     // ---- finalize: divide by the denominator, store the row (zeros for padded rows)
-    const float l_tot = l + __shfl_xor(l, 32);
+    const float l_tot = (l + __shfl_xor(l, 32)) * 65535.0f;
     const float inv = (row_valid && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
     const long long ooff = out_row_offset<D>(a, bh, h, head_rows, row, row_valid);
     if (ooff >= 0) {
