@@ -19,3 +19,23 @@ def test_spill_report_names_only_kernels_with_scratch():
     assert spilling_kernels(REPORT) == [("_ZN4paro6kern_bEv", 216)]
     assert spilling_kernels("") == []
     assert spilling_kernels(REPORT.replace("216", "0")) == []
+
+
+def test_kernels_contain_no_inline_assembly_instructions():
+    """An instruction written as inline assembly is invisible to the compiler's hazard handling (a
+    conversion placed directly behind the exponential it consumes needs a wait state that only
+    compiler-visible instructions get), so the kernels use builtins; the one `asm` left is the empty
+    optimization barrier."""
+    import glob
+    import os
+    import re
+
+    from paper_2506_16054_amd.build import CSRC
+
+    found = []
+    for path in sorted(glob.glob(os.path.join(CSRC, "*"))):
+        text = open(path).read()
+        for m in re.finditer(r"\basm\s*(?:volatile)?\s*\(\s*\"([^\"]*)\"", text):
+            if m.group(1).strip():
+                found.append((os.path.basename(path), m.group(1)))
+    assert found == [], found
