@@ -266,13 +266,12 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     };
 
     v4i kreg[NKC], vreg[NVC];
-    float sk_reg = 0.0f, sv_reg = 0.0f;  // scales of the block whose tiles sit in kreg / vreg
+    int j_reg = 0;  // column block whose tiles sit in kreg / vreg (wave-uniform)
     auto gload = [&](int t) {
         const int j = col_of(t);
+        j_reg = j;
         const uint8_t* kp = kbase + (size_t)j * (BLK * D / KPACK);
         const uint8_t* vp = vbase + (size_t)j * (BLK * D / VPACK);
-        sk_reg = skp[j];
-        sv_reg = svp[j];
 #pragma unroll
         for (int c = 0; c < NKC; ++c) kreg[c] = *(const v4i*)(kp + 16 * (tid + NT * c));
 #pragma unroll
@@ -338,13 +337,16 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     //   V_{t+1} is stored right after barrier t      - every wavefront finished reading V_{t-1}
     //                                                  before it arrived at barrier t;
     //   the registers are refilled from global memory (block t+2) after both stores.
+    // The scales of a block are fetched one block ahead of their use (behind the barrier of the block
+    // before), straight into the registers the next iteration reads: its column index is carried in a
+    // scalar register from the tile prefetch, so nothing per lane rotates from block to block.
     float sk_cur = 0.0f, sv_cur = 0.0f;  // scales of block t
     if (cnt > 0) {
         gload(0);
         lstore_k(0);
         lstore_v(0);
-        sk_cur = sk_reg;
-        sv_cur = sv_reg;
+        sk_cur = skp[j_reg];
+        sv_cur = svp[j_reg];
     }
     if (cnt > 1) gload(1);
     __syncthreads();
@@ -421,7 +423,9 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
             if (lane == 0) tile_e[t & 1][w] = eb;
         }
         __syncthreads();
-        const float sk_next = sk_reg, sv_next = sv_reg;  // scales of block t+1, fetched with its tiles
+        // scales of block t+1 (j_reg still names it: the prefetch of block t+2 comes below)
+        // (behind the last block it names that block again: a harmless reload)
+        const float sk_next = skp[j_reg], sv_next = svp[j_reg];
         if (t + 1 < cnt) lstore_v(next);
         if (((t + 2) & 63) == 0) {  // block t+2 opens a new chunk of 64 column indices
             cols_cur = cols_nxt;
