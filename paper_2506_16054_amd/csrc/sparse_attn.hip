@@ -179,8 +179,9 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     const int g = lane >> 5;
 
     const int* rp = a.row_ptr + (size_t)h * (a.kblocks + 1) + i;
-    const int beg = min(max(rp[0], 0), a.nnz);
-    const int end = min(max(rp[1], beg), a.nnz);
+    // (the same for every lane: kept in scalar registers, so the loop control costs no vector work)
+    const int beg = __builtin_amdgcn_readfirstlane(min(max(rp[0], 0), a.nnz));
+    const int end = __builtin_amdgcn_readfirstlane(min(max(rp[1], beg), a.nnz));
     const int cnt = end - beg;
     const int* cols = a.col_idx + beg;
     // A row block that attends more than half of all column blocks (text rows of an image model,
@@ -453,8 +454,6 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
         }
         // weight of this block's terms in the stored sums: sP * 2^(m' - m_ref)
         const float w_blk = __builtin_amdgcn_exp2f(e + growth - LOG2_QMAXP);
-        // exponent offset: X - m' - e + log2(qmaxP), so that the tile maximum maps to qmaxP
-        const float off = LOG2_QMAXP - m_new - e;
         m = m_new;
 
         // ---- E = qmaxP * 2^(X - m' - e); row sum; round half to even and pack as B operand
@@ -462,8 +461,9 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
         v4i pf[KT];
         // E is formed divided by 65535, so that v_cvt_pknorm_u16_f32 (which rounds x * 65535 to the
         // nearest 16-bit integer, two values per instruction) yields the codes; one byte permute
-        // packs four of them.  The row sum carries the same factor, undone in the weight.
-        const float off_n = off - 15.999977986052736f;  // log2(65535)
+        // packs four of them.  The row sum carries the same factor, undone once per row.
+        // Exponent offset: X - m' - e + log2(qmaxP) - log2(65535): the tile maximum maps to qmaxP / 65535.
+        const float off_n = (LOG2_QMAXP - 15.999977986052736f) - m_new - e;
 #pragma unroll
         for (int T = 0; T < KT; ++T) {
 #pragma unroll
