@@ -578,8 +578,8 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? 3 : 2)) void attn_bf16_kernel(A
     const int g = lane >> 5;
 
     const int* rp = a.row_ptr + (size_t)h * (a.kblocks + 1) + i;
-    const int beg = min(max(rp[0], 0), a.nnz);
-    const int end = min(max(rp[1], beg), a.nnz);
+    const int beg = __builtin_amdgcn_readfirstlane(min(max(rp[0], 0), a.nnz));  // uniform: scalar loop control
+    const int end = __builtin_amdgcn_readfirstlane(min(max(rp[1], beg), a.nnz));
     const int cnt = end - beg;
     const int* cols = a.col_idx + beg;
 
@@ -609,21 +609,20 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? 3 : 2)) void attn_bf16_kernel(A
     };
 
     v4i kreg[NKC], vreg[NVC];
+    // LDS store offsets: piece cc of a thread lies a whole number of rows below its piece 0, so one
+    // address per tile serves all pieces through immediate offsets
+    static_assert((16 * NT) % (2 * D) == 0 && (16 * NT) % (2 * BLK) == 0, "pieces must be whole rows apart");
+    const int k_off = ((16 * tid) / (2 * D)) * KSTR + (16 * tid) % (2 * D);
+    const int v_off = KBYTES + ((16 * tid) / (2 * BLK)) * VSTR + (16 * tid) % (2 * BLK);
     auto lstore_k = [&](int stage) {
-        uint8_t* ks = lds + stage * STAGE;
+        uint8_t* dst0 = lds + stage * STAGE + k_off;
 #pragma unroll
-        for (int cc = 0; cc < NKC; ++cc) {
-            const int o = 16 * (tid + NT * cc);
-            *(v4i*)(ks + (o / (2 * D)) * KSTR + (o % (2 * D))) = kreg[cc];
-        }
+        for (int cc = 0; cc < NKC; ++cc) *(v4i*)(dst0 + cc * (16 * NT / (2 * D)) * KSTR) = kreg[cc];
     };
     auto lstore_v = [&](int stage) {
-        uint8_t* vs = lds + stage * STAGE + KBYTES;
+        uint8_t* dst0 = lds + stage * STAGE + v_off;
 #pragma unroll
-        for (int cc = 0; cc < NVC; ++cc) {
-            const int o = 16 * (tid + NT * cc);
-            *(v4i*)(vs + (o / (2 * BLK)) * VSTR + (o % (2 * BLK))) = vreg[cc];
-        }
+        for (int cc = 0; cc < NVC; ++cc) *(v4i*)(dst0 + cc * (16 * NT / (2 * BLK)) * VSTR) = vreg[cc];
     };
 
     // The exponentials are taken against a fixed reference per row (its maximum after the first
