@@ -319,6 +319,8 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 
     float m = -INFINITY;  // running row maximum, log2 units
     float m_ref = -INFINITY;  // the maximum the stored sums are expressed against (set by the first block)
+    constexpr float kLog2_65535 = 15.999977986052736f;
+    float w_base = INFINITY;  // -log2(65535) - m_ref
     float l = 0.0f;       // this lane's share of the running denominator, divided by 65535 * 2^(m - m_ref)
     float acc[DT][16];
 #pragma unroll
@@ -441,7 +443,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
         const float e = __uint_as_float(eb);
         // The first block of a row finds m_ref = -inf: growth = +inf takes the branch below, which
         // scales the (zero) sums by 2^-inf = 0 and makes the block's maximum the reference.
-        float growth = m_new - m_ref;
+        const float growth = m_new - m_ref;
         if (__builtin_amdgcn_ballot_w64(growth > 64.0f) != 0) {  // keep the stored sums far from overflow
             const float down = __builtin_amdgcn_exp2f(-growth);
             l *= down;
@@ -450,10 +452,8 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[dt][r] *= down;
             m_ref = m_new;
-            growth = 0.0f;
+            w_base = -kLog2_65535 - m_new;
         }
-        // weight of this block's terms in the stored sums: sP * 2^(m' - m_ref)
-        const float w_blk = __builtin_amdgcn_exp2f(e + growth - LOG2_QMAXP);
         m = m_new;
 
         // ---- E = qmaxP * 2^(X - m' - e); row sum; round half to even and pack as B operand
@@ -463,7 +463,10 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
         // nearest 16-bit integer, two values per instruction) yields the codes; one byte permute
         // packs four of them.  The row sum carries the same factor, undone once per row.
         // Exponent offset: X - m' - e + log2(qmaxP) - log2(65535): the tile maximum maps to qmaxP / 65535.
-        const float off_n = (LOG2_QMAXP - 15.999977986052736f) - m_new - e;
+        const float off_n = (LOG2_QMAXP - kLog2_65535) - m_new - e;
+        // weight of this block's terms in the stored sums, sP * 2^(m' - m_ref) = 2^(e + m' - m_ref - log2(qmaxP)),
+        // written against the offset above: the part that depends on m_ref alone changes only with m_ref
+        const float w_blk = __builtin_amdgcn_exp2f(w_base - off_n);
 #pragma unroll
         for (int T = 0; T < KT; ++T) {
 #pragma unroll
