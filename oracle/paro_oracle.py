@@ -195,21 +195,21 @@ def sparse_attention_head(
     col_idx: np.ndarray,
     qmax_p: Optional[int],
     row_blocks: Optional[Sequence[int]] = None,
-    tie_tol: float = 0.0,
-    diag: Optional[dict] = None,
+    observer=None,
 ) -> np.ndarray:
     """One head.  qc/kc/vc [npad, d] hold integer codes (or plain values with scales of 1 for an
     unquantized operand); sq/sk/sv [k] are the per-block scales.  ``qmax_p`` None leaves P
     unquantized.  Returns Op float64 [npad, d]; rows of padded tokens and of row blocks that are
     not listed in ``row_blocks`` stay zero.  A row block with no live block gives zeros.
 
-    Rounding ties.  The P codes are an integer decision taken on floating-point values.  An
-    implementation that evaluates Pt / sP with relative error up to ``tie_tol`` may legitimately
-    round an entry that lies within that error of a half-integer to the other neighbour.  When
-    ``diag`` is a dict, ``diag["flip_risk"]`` [npad, d] receives, per output element, the exact
-    first-order bound on the change such flips can cause: every near-tie entry contributes
-    sP * sv * |Vc| of its key, carried through the same rescaling recurrence as the accumulator
-    and divided by the same denominator.  It does not alter the returned result.
+    The live blocks of a row are visited in the order in which the list holds them (ascending
+    column block for a list made by ``mask_to_blocklist``); with P quantized per visit against the
+    running row maxima the result depends on that order (Sec. 4.3 (1),(2)).
+
+    ``observer``, if given, is shown the intermediate quantities and changes nothing:
+    ``observer.visit(i, j, p, codes, s_p, alpha)`` after every visited block (P tile, its integer
+    codes and scale - None when P is not quantized - and the rescale factor of the earlier sums)
+    and ``observer.row_block_done(i, l)`` with the final denominators of row block i.
     """
     npad, d = qc.shape
     k = npad // block
@@ -218,7 +218,6 @@ def sparse_attention_head(
     vf = vc.astype(np.float64)
     inv_sqrt_d = 1.0 / math.sqrt(d)
     out = np.zeros((npad, d), np.float64)
-    risk_out = np.zeros((npad, d), np.float64) if diag is not None else None
     todo = range(k) if row_blocks is None else row_blocks
     for i in todo:
         r0 = i * block
@@ -228,7 +227,6 @@ def sparse_attention_head(
         m = np.full(n_rows, -np.inf)
         l = np.zeros(n_rows)
         acc = np.zeros((n_rows, d))
-        risk = np.zeros((n_rows, d))
         q_i = qf[r0 : r0 + n_rows]
         for t in range(int(row_ptr[i]), int(row_ptr[i + 1])):
             j = int(col_idx[t])
@@ -243,22 +241,19 @@ def sparse_attention_head(
             p = np.exp(x - m_new[:, None])
             l = alpha * l + p.sum(axis=1)
             if qmax_p is None:
+                codes, s_p = None, None
                 pv = p @ (vf[c0 : c0 + n_cols] * float(sv[j]))
             else:
                 codes, s_p = quantize_p_tile(p, np.ones_like(p, bool), qmax_p)
                 pv = (codes @ vf[c0 : c0 + n_cols]) * (s_p * float(sv[j]))
-                if risk_out is not None and s_p > 0:
-                    e = p / s_p
-                    near = np.abs(np.abs(e - np.rint(e)) - 0.5) <= tie_tol * e + 1e-12
-                    risk = alpha[:, None] * risk + (near.astype(np.float64) @ np.abs(vf[c0 : c0 + n_cols])) * (s_p * float(sv[j]))
             acc = alpha[:, None] * acc + pv
             m = m_new
+            if observer is not None:
+                observer.visit(i, j, p, codes, s_p, alpha)
         nz = l > 0
         out[r0 : r0 + n_rows][nz] = acc[nz] / l[nz, None]
-        if risk_out is not None:
-            risk_out[r0 : r0 + n_rows][nz] = risk[nz] / l[nz, None]
-    if diag is not None:
-        diag["flip_risk"] = risk_out
+        if observer is not None:
+            observer.row_block_done(i, l)
     return out
 
 

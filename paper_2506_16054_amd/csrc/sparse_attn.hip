@@ -118,6 +118,15 @@ constexpr int kAccBiasI = 0x4B400000;
 constexpr float kAccBiasF = 12582912.0f;
 __device__ inline float int_result(int raw) { return __int_as_float(raw) - kAccBiasF; }
 
+#ifndef PARO_FOLD_S
+#define PARO_FOLD_S 0
+#endif
+#ifndef PARO_ALT_O
+#define PARO_ALT_O 0
+#endif
+#ifndef PARO_ABLATE
+#define PARO_ABLATE 0
+#endif
 #ifndef PARO_ATTN_WAVES_D64
 #define PARO_ATTN_WAVES_D64 3  // wavefronts per SIMD the register allocation must allow, d = 64
 #endif
@@ -319,7 +328,9 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 
     float m = -INFINITY;  // running row maximum, log2 units
     float m_ref = -INFINITY;  // the maximum the stored sums are expressed against (set by the first block)
-    constexpr float kLog2_65535 = 15.999977986052736f;
+    constexpr bool ALT_O = PARO_ALT_O && D == 64;
+    constexpr float kLogNorm = ALT_O ? 14.999955971769423f : 15.999977986052736f;  // log2(32767) signed / log2(65535)
+    constexpr float kNorm = ALT_O ? 32767.0f : 65535.0f;
     float w_base = INFINITY;  // -log2(65535) - m_ref
     float l = 0.0f;       // this lane's share of the running denominator, divided by 65535 * 2^(m - m_ref)
     float acc[DT][16];
@@ -333,6 +344,13 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc_init[r] = kAccBiasI;
     asm volatile("" : "+v"(acc_init));  // opaque to the optimizer: not re-created per block
+    v16i acc_init_neg;
+    float bias_sum = 0.0f;  // sum of the biases carried by acc (the same for all of a lane's elements)
+    if constexpr (ALT_O) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_init_neg[r] = (int)0xCB400000;
+        asm volatile("" : "+v"(acc_init_neg));
+    }
 
     // LDS ring of two stages, one barrier per live block (placed after the row maxima):
     //   K_{t+1} is stored at the top of iteration t  - every wavefront finished reading K_{t-1}
@@ -379,8 +397,10 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     // One live block.  TAIL selects the variant that masks keys past N (only the last column
     // block of a ragged sequence needs it; keeping it out of the common path saves two
     // instructions per logit).
-    auto step = [&](auto tail_tag, int t) {
+    auto step = [&](auto tail_tag, auto neg_tag, int t) {
         constexpr bool TAIL = decltype(tail_tag)::value;
+        constexpr bool NEG = decltype(neg_tag)::value;  // odd visits: P codes negated, output bias negative
+        (void)NEG;
         const int next = stage ^ 1;
         if (t + 1 < cnt) lstore_k(next);
 
@@ -396,7 +416,8 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 const v4i kf = *(const v4i*)(ks + (32 * T + n) * KSTR + 32 * s + 16 * g);
-                sacc[T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf[s], sacc[T], 0, 0, 0);
+                if constexpr (!(PARO_ABLATE & 32)) sacc[T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf[s], sacc[T], 0, 0, 0);
+                else sacc[T][s] ^= kf[0] & 0xff;
             }
         }
         // Raw accumulator value of a masked logit: it loses every maximum (real values carry the
@@ -416,7 +437,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 #pragma unroll
         for (int T = 0; T < KT; ++T)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) part[r & 3] = max(part[r & 3], sacc[T][r]);
+            for (int r = 0; r < ((PARO_ABLATE & 4) ? 1 : 16); ++r) part[r & 3] = max(part[r & 3], sacc[T][r]);
         const float ymax = c * int_result(xor32_max(max(max(part[0], part[1]), max(part[2], part[3]))));
         const float m_new = fmaxf(m, ymax);
         // e = log2 of the largest entry of the Pt tile = max over valid rows of (row maximum of
@@ -451,8 +472,9 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[dt][r] *= down;
+            if constexpr (ALT_O) bias_sum *= down;
             m_ref = m_new;
-            w_base = -kLog2_65535 - m_new;
+            w_base = -kLogNorm - m_new;
         }
         m = m_new;
 
@@ -463,10 +485,22 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
         // nearest 16-bit integer, two values per instruction) yields the codes; one byte permute
         // packs four of them.  The row sum carries the same factor, undone once per row.
         // Exponent offset: X - m' - e + log2(qmaxP) - log2(65535): the tile maximum maps to qmaxP / 65535.
-        const float off_n = (LOG2_QMAXP - kLog2_65535) - m_new - e;
+        const float off_n = (LOG2_QMAXP - kLogNorm) - m_new - e;
         // weight of this block's terms in the stored sums, sP * 2^(m' - m_ref) = 2^(e + m' - m_ref - log2(qmaxP)),
         // written against the offset above: the part that depends on m_ref alone changes only with m_ref
+#if PARO_FOLD_S
+        // c * (B + S) + off_f with off_f = fl(off_n - c*B): the two roundings (of c*B and of the difference) are
+        // recovered exactly (fma residual, two-sum) and returned to the block weight.
+        const float cb_hi = c * kAccBiasF;
+        const float cb_lo = fmaf(c, kAccBiasF, -cb_hi);
+        const float off_f = off_n - cb_hi;
+        const float bb = off_f - off_n;
+        const float terr = (off_n - (off_f - bb)) + (-cb_hi - bb);
+        const float delta = cb_lo - terr;  // E is formed as E_exact * 2^delta
+        const float w_blk = __builtin_amdgcn_exp2f((w_base - off_n) - delta);
+#else
         const float w_blk = __builtin_amdgcn_exp2f(w_base - off_n);
+#endif
 #pragma unroll
         for (int T = 0; T < KT; ++T) {
 #pragma unroll
@@ -474,17 +508,33 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
                 float ev[4];
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
-                    ev[p] = __builtin_amdgcn_exp2f(fmaf(int_result(sacc[T][4 * qd + p]), c, off_n));
+#if PARO_FOLD_S
+                    ev[p] = fmaf(__int_as_float(sacc[T][4 * qd + p]), c, off_f);
+#else
+                    ev[p] = fmaf(int_result(sacc[T][4 * qd + p]), c, off_n);
+#endif
+                    if constexpr (!(PARO_ABLATE & 1)) ev[p] = __builtin_amdgcn_exp2f(ev[p]);
                     if constexpr (TAIL) {
                         if (32 * T + 8 * qd + 4 * g + p >= a.n_tokens - (a.kblocks - 1) * BLK) ev[p] = 0.0f;
                     }
-                    rs = (T == 0 && qd == 0 && p == 0) ? ev[p] : rs + ev[p];
+                    if constexpr (!(PARO_ABLATE & 64)) rs = (T == 0 && qd == 0 && p == 0) ? ev[p] : rs + ev[p];
+                    else if (T == 0 && qd == 0 && p == 0) rs = ev[p];
                 }
                 // (the builtin, not inline assembly: the instruction consumes results of the
                 // transcendental unit, and only instructions the compiler can see get the wait state
                 // that this needs when they follow the exponential directly)
-                const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[0], ev[1]));
-                const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[2], ev[3]));
+                unsigned lo, hi;
+                if constexpr ((PARO_ABLATE & 2) != 0) {
+                    pf[T][qd] = __float_as_int(ev[0]) ^ __float_as_int(ev[1]) ^ __float_as_int(ev[2]) ^ __float_as_int(ev[3]);
+                    continue;
+                }
+                if constexpr (ALT_O) {
+                    lo = __builtin_bit_cast(unsigned, NEG ? __builtin_amdgcn_cvt_pknorm_i16(-ev[0], -ev[1]) : __builtin_amdgcn_cvt_pknorm_i16(ev[0], ev[1]));
+                    hi = __builtin_bit_cast(unsigned, NEG ? __builtin_amdgcn_cvt_pknorm_i16(-ev[2], -ev[3]) : __builtin_amdgcn_cvt_pknorm_i16(ev[2], ev[3]));
+                } else {
+                    lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[0], ev[1]));
+                    hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[2], ev[3]));
+                }
                 pf[T][qd] = (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u);
             }
         }
@@ -494,15 +544,19 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
         const float sv_eff = w_blk * sv_cur * (PVBITS == 4 ? 0.0625f : 1.0f);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-            v16i o = acc_init;
+            v16i o = (ALT_O && NEG) ? acc_init_neg : acc_init;
 #pragma unroll
             for (int T = 0; T < KT; ++T) {
                 const v4i vf = *(const v4i*)(vs + (32 * dt + n) * VSTR + 32 * T + 16 * g);
-                o = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf[T], o, 0, 0, 0);
+                if constexpr (!(PARO_ABLATE & 16)) o = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf[T], o, 0, 0, 0);
+                else o[T] ^= vf[0] & pf[T][0];
             }
+            // ALT_O: the register read as a float is +-B + result: the bias alternates in sign from visit to visit and
+            // is tracked per lane (bias_sum), so the running sums stay near the size of one block's bias
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[dt][r] = fmaf(int_result(o[r]), sv_eff, acc[dt][r]);
+            for (int r = 0; r < ((PARO_ABLATE & 8) ? 2 : 16); ++r) acc[dt][r] = fmaf(ALT_O ? __int_as_float(o[r]) : int_result(o[r]), sv_eff, acc[dt][r]);
         }
+        if constexpr (ALT_O) bias_sum = fmaf(NEG ? -kAccBiasF : kAccBiasF, sv_eff, bias_sum);
         sk_cur = sk_next;
         sv_cur = sv_next;
         stage = next;
@@ -512,11 +566,26 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     // reads the list directly (once per workgroup).
     const bool has_tail = (a.n_tokens % BLK) != 0 && cnt > 0 && min(max(cols[cnt - 1], 0), a.kblocks - 1) == a.kblocks - 1;
     const int cnt_main = has_tail ? cnt - 1 : cnt;
-    for (int t = 0; t < cnt_main; ++t) step(std::false_type{}, t);
-    if (has_tail) step(std::true_type{}, cnt - 1);
+    if constexpr (ALT_O) {
+        for (int t = 0; t < cnt_main; t += 2) {
+            step(std::false_type{}, std::false_type{}, t);
+            if (t + 1 < cnt_main) step(std::false_type{}, std::true_type{}, t + 1);
+        }
+        if (has_tail) {
+            if ((cnt - 1) & 1) step(std::true_type{}, std::true_type{}, cnt - 1);
+            else step(std::true_type{}, std::false_type{}, cnt - 1);
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[dt][r] -= bias_sum;
+    } else {
+        for (int t = 0; t < cnt_main; ++t) step(std::false_type{}, std::false_type{}, t);
+        if (has_tail) step(std::true_type{}, std::false_type{}, cnt - 1);
+    }
 
     // ---- finalize: divide by the denominator, store the row (zeros for padded rows)
-    const float l_tot = (l + __shfl_xor(l, 32)) * 65535.0f;
+    const float l_tot = (l + __shfl_xor(l, 32)) * kNorm;
     const float inv = (row_valid && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
     const long long ooff = out_row_offset<D>(a, bh, h, head_rows, row, row_valid);
     if (ooff >= 0) {

@@ -15,10 +15,50 @@ def blocklist_for(w, masks):
     return bits, row_ptr, col_idx
 
 
-# Relative error bound of the HIP kernel's evaluation of Pt / sP (fp32 fma of the logit, the
-# hardware exp2 and fp32 running maxima); P codes whose exact value lies this close to a
-# rounding tie may legitimately come out as either neighbour.
-KERNEL_TIE_TOL = 2e-5
+# Rounding ties of the P codes.  A P code is an integer decision taken on floating-point values
+# (E = Pt / sP): an implementation whose E carries a relative error up to KERNEL_TIE_TOL may round an
+# entry that lies within that error of a half-integer to the other neighbour, and one such flip moves
+# an output element by sP * sv * |Vc| / l of its key - far more than the evaluation error itself.
+# The figure is the error of the HIP kernel's E, derived from its arithmetic: the logit is one fp32
+# fma of exact integers (relative 2^-24 of an exponent of at most ~2^7, i.e. <= 8e-6 * ln 2 in E), the
+# hardware exp2 is accurate to about 1 ulp (1.2e-7), and the offset of that fma (running maximum, tile
+# exponent and the folded accumulator bias, magnitude c * 1.5 * 2^23 <= ~2^13) is rounded to fp32 once
+# (<= 2^-12 / 2 * ln 2 = 8.5e-5 in E).  1e-4 covers the sum.
+KERNEL_TIE_TOL = 1e-4
+
+
+class TieRisk:
+    """Observer of ``po.sparse_attention_head``: per output element, the first-order bound on what
+    flipping every P code within ``tol`` (relative) of a rounding tie can change.  Every near-tie
+    entry contributes sP * sv * |Vc| of its key; the contributions are carried through the same
+    rescaling recurrence as the accumulator and divided by the same denominator."""
+
+    def __init__(self, vc, sv, block, n_valid, tol):
+        self.absv = np.abs(np.asarray(vc, np.float64))
+        self.sv = np.asarray(sv, np.float64)
+        self.block, self.n_valid, self.tol = block, n_valid, tol
+        self.out = np.zeros(self.absv.shape, np.float64)
+        self._risk = None
+        self._row = None
+
+    def visit(self, i, j, p, codes, s_p, alpha):
+        if self._row != i:
+            self._row, self._risk = i, np.zeros((p.shape[0], self.absv.shape[1]))
+        self._risk = alpha[:, None] * self._risk
+        if s_p is None or s_p <= 0:
+            return
+        c0 = j * self.block
+        e = p / s_p
+        near = np.abs(np.abs(e - np.rint(e)) - 0.5) <= self.tol * e + 1e-12
+        self._risk += (near.astype(np.float64) @ self.absv[c0 : c0 + p.shape[1]]) * (s_p * self.sv[j])
+
+    def row_block_done(self, i, l):
+        if self._row != i:
+            return
+        r0 = i * self.block
+        nz = l > 0
+        self.out[r0 : r0 + l.shape[0]][nz] = self._risk[nz] / l[nz, None]
+        self._row = None
 
 
 def oracle_head(w, q, k, v, perm_id, row_ptr_h, col_idx, row_blocks=None):
@@ -30,11 +70,10 @@ def oracle_head(w, q, k, v, perm_id, row_ptr_h, col_idx, row_blocks=None):
     vc, sv = po.prepare_operand(v, idx, w.npad, w.block, w.bits_pv)
     out.update(qc=qc, sq=sq, kc=kc, sk=sk, vc=vc, sv=sv)
     qmax_p = None if w.bits_pv in (0, 16) else po.qmax_of(w.bits_pv)
-    diag = {}
-    op = po.sparse_attention_head(qc, sq, kc, sk, vc, sv, w.N, w.block, row_ptr_h, col_idx, qmax_p, row_blocks,
-                                  tie_tol=KERNEL_TIE_TOL, diag=diag)
+    risk = TieRisk(vc, sv, w.block, w.N, KERNEL_TIE_TOL)
+    op = po.sparse_attention_head(qc, sq, kc, sk, vc, sv, w.N, w.block, row_ptr_h, col_idx, qmax_p, row_blocks, observer=risk)
     out["op"] = op
-    out["flip_risk"] = diag["flip_risk"]
+    out["flip_risk"] = risk.out
     out["o"] = po.unpermute(op, idx)
     return out
 
@@ -45,14 +84,78 @@ def rel_l2(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
+# Share of the elements that may exceed the plain element-wise bar through a flipped near-tie P code
+# (seen: none with 8-bit P codes, 4 of 1.1 million on a whole head with 4-bit P codes, where one flip moves
+# an element by up to a seventh of its largest term).
+MAX_TIE_EXCESS = 2e-5
+
+
 def check_attention(got, ref, risk, max_abs, rel, what=""):
-    """Element-wise and relative-L2 bar, widened only by what flips of near-tie P codes can cause."""
+    """The stated bar: relative L2 <= rel on everything, plainly; |got - ref| <= max_abs on every
+    element that no near-tie P code can reach (risk == 0).  The remaining elements may exceed max_abs
+    by at most their tie allowance, and those that do are counted, reported and bounded."""
     got, ref, risk = (np.asarray(a, np.float64) for a in (got, ref, risk))
     diff = np.abs(got - ref)
-    worst = float(np.max(diff - risk))
-    assert worst <= max_abs, "%s: max-abs %.3e beyond tie allowance exceeds %.1e" % (what, worst, max_abs)
-    lhs = float(np.linalg.norm(got - ref))
-    rhs = rel * float(np.linalg.norm(ref)) + float(np.linalg.norm(risk))
-    assert lhs <= rhs, "%s: L2 error %.3e exceeds %.3e" % (what, lhs, rhs)
-    risky_rows = float(np.mean(risk.max(axis=-1) > 0))
-    return {"max_abs": float(diff.max()), "rel_l2": lhs / max(float(np.linalg.norm(ref)), 1e-300), "risky_rows": risky_rows}
+    ref_norm = max(float(np.linalg.norm(ref)), 1e-300)
+    rel_err = float(np.linalg.norm(got - ref)) / ref_norm
+    assert rel_err <= rel, "%s: relative L2 %.3e exceeds %.1e" % (what, rel_err, rel)
+    safe = risk == 0
+    worst_safe = float(diff[safe].max()) if safe.any() else 0.0
+    assert worst_safe <= max_abs, "%s: max-abs %.3e exceeds %.1e where no P code is near a tie" % (what, worst_safe, max_abs)
+    over = diff > max_abs
+    n_over = int(over.sum())
+    assert not (over & (diff - risk > max_abs)).any(), "%s: max-abs %.3e beyond the tie allowance" % (what, float((diff - risk).max()))
+    assert n_over <= int(np.ceil(MAX_TIE_EXCESS * diff.size)), "%s: %d of %d elements beyond %.1e" % (what, n_over, diff.size, max_abs)
+    st = {"max_abs": float(diff.max()), "rel_l2": rel_err, "n_over": n_over, "risky_share": float(np.mean(~safe))}
+    print("%s: max_abs %.2e rel_l2 %.2e, %d elements over %.0e (tie allowance), %.2f%% of elements reachable by a tie"
+          % (what or "attention", st["max_abs"], rel_err, n_over, max_abs, 100 * st["risky_share"]))
+    return st
+
+
+# ---------------------------------------------------------------------------------------------
+# Whole heads of a full-size workload: the oracle over every row block, spread over worker
+# processes.  The workers are started with the "spawn" method (fresh interpreters that import only
+# numpy and the oracle), so they are safe to start from a process that has already initialised the GPU.
+# ---------------------------------------------------------------------------------------------
+def _oracle_rows_job(job):
+    (dims, q, k, v, perm_id, row_ptr_h, col_idx, row_blocks, tol) = job
+    F, Hg, Wg, T_text, n, npad, block, bits_qk, bits_pv = dims
+    idx = po.perm_index(F, Hg, Wg, T_text, int(perm_id))
+    qc, sq = po.prepare_operand(q, idx, npad, block, bits_qk)
+    kc, sk = po.prepare_operand(k, idx, npad, block, bits_qk)
+    vc, sv = po.prepare_operand(v, idx, npad, block, bits_pv)
+    qmax_p = None if bits_pv in (0, 16) else po.qmax_of(bits_pv)
+    risk = TieRisk(vc, sv, block, n, tol)
+    op = po.sparse_attention_head(qc, sq, kc, sk, vc, sv, n, block, row_ptr_h, col_idx, qmax_p, row_blocks, observer=risk)
+    rows = np.concatenate([np.arange(i * block, min((i + 1) * block, n)) for i in row_blocks])
+    return rows, op[rows], risk.out[rows]
+
+
+def oracle_whole_heads(w, heads, qkv_of_head, perm_ids, row_ptr, col_idx, workers=None):
+    """{h: (op [npad, d], flip_risk [npad, d])} for every row block of the listed heads.
+    ``qkv_of_head(h)`` returns the head's (q, k, v) as float32 [N, d] arrays; ``row_ptr`` is [nh, k+1]."""
+    import multiprocessing as mp
+    import os
+    from concurrent.futures import ProcessPoolExecutor
+
+    if workers is None:
+        workers = max(1, min(16, len(os.sched_getaffinity(0))))
+    dims = (w.F, w.Hg, w.Wg, w.T_text, w.N, w.npad, w.block, w.bits_qk, w.bits_pv)
+    jobs, owner = [], []
+    for h in heads:
+        q, k, v = qkv_of_head(h)
+        live = np.diff(row_ptr[h])
+        # deal the row blocks to the workers heaviest first, so the chunks carry equal work
+        order = np.argsort(-live, kind="stable")
+        per = max(1, workers // max(1, len(heads))) if len(heads) < workers else 1
+        chunks = [sorted(int(i) for i in order[c::per]) for c in range(per)]
+        for rows in chunks:
+            if rows:
+                jobs.append((dims, q, k, v, int(perm_ids[h]), row_ptr[h], col_idx, rows, KERNEL_TIE_TOL))
+                owner.append(h)
+    out = {h: (np.zeros((w.npad, w.d)), np.zeros((w.npad, w.d))) for h in heads}
+    with ProcessPoolExecutor(max_workers=workers, mp_context=mp.get_context("spawn")) as ex:
+        for h, (rows, op_rows, risk_rows) in zip(owner, ex.map(_oracle_rows_job, jobs)):
+            out[h][0][rows] = op_rows
+            out[h][1][rows] = risk_rows
+    return out

@@ -288,28 +288,92 @@ def test_cast_output_bf16_rounds_to_nearest_even():
     assert po.cast_output(x, "f32")[4] == np.float32(-3.14159)
 
 
-def test_flip_risk_bounds_the_effect_of_a_rounding_tie():
+def _order_case():
+    """Hand-worked case in which the visiting order decides the result (Sec. 4.3 (1),(2): the P tile
+    is quantized as one group against the running row maxima at the time of the visit).
+
+    b = 2, d = 1, one row block with queries A = +1 and B = -1, scales chosen so that a logit is
+    (q * k) * ln 2, i.e. P entries are powers of two.  Column block 0 holds keys (2, 0), column
+    block 1 keys (-2, 0); V codes are (1, 2 | 3, 4), all scales 1.
+
+    Ascending (block 0, then block 1):
+      block 0: A sees logits (2, 0) ln2 -> m = 2, P = (1, 1/4);  B sees (-2, 0) -> m = 0, P = (1/4, 1);
+               tile maximum 1, sP = 1/127, codes A (127, 32) [31.75 -> 32], B (32, 127); l = 5/4 each.
+      block 1: A sees (-2, 0): m stays 2, P = (1/16, 1/4);  B sees (2, 0): m -> 2, earlier sums x 1/4,
+               P = (1, 1/4); tile maximum 1, codes A (8, 32) [7.9375 -> 8], B (127, 32).
+      l = 5/4 + 5/16 = 25/16 (A) and 5/16 + 5/4 = 25/16 (B).
+      numerator A = (127*1 + 32*2) + (8*3 + 32*4) = 343,  B = (32*1 + 127*2)/4 + (127*3 + 32*4) = 580.5
+    Descending (block 1, then block 0) the same steps give
+      numerator A = (32*3 + 127*4)/4 + (127*1 + 32*2) = 342,  B = (127*3 + 32*4) + (8*1 + 32*2) = 581.
+    Each output is numerator / 127 / (25/16)."""
+    ln2 = np.float32(math.log(2.0))
+    q = np.array([[1.0], [-1.0], [0.0], [0.0]])
+    k = np.array([[2.0], [0.0], [-2.0], [0.0]])
+    v = np.array([[1.0], [2.0], [3.0], [4.0]])
+    sq = np.array([ln2, 1.0], np.float32)
+    ones = np.ones(2, np.float32)
+    return q, sq, k, ones, v, ones
+
+
+def test_live_blocks_are_visited_in_ascending_order_hand_worked():
+    q, sq, k, sk, v, sv = _order_case()
+    rp = np.array([0, 2, 2], np.int32)
+    o = po.sparse_attention_head(q, sq, k, sk, v, sv, 4, 2, rp, np.array([0, 1], np.int32), 127)
+    l = 25.0 / 16.0
+    assert o[0, 0] == pytest.approx(343.0 / 127.0 / l, rel=1e-6)
+    assert o[1, 0] == pytest.approx(580.5 / 127.0 / l, rel=1e-6)
+    assert np.all(o[2:] == 0)
+    # the descending visit is a different result, by more than the tolerance of the check above
+    assert abs(343.0 - 342.0) / 343.0 > 1e-3 and abs(581.0 - 580.5) / 581.0 > 5e-4
+
+
+def test_block_list_order_is_the_visiting_order_hand_worked():
+    # the same case with the list holding the blocks in descending order: the other hand-worked values
+    q, sq, k, sk, v, sv = _order_case()
+    rp = np.array([0, 2, 2], np.int32)
+    o = po.sparse_attention_head(q, sq, k, sk, v, sv, 4, 2, rp, np.array([1, 0], np.int32), 127)
+    l = 25.0 / 16.0
+    assert o[0, 0] == pytest.approx(342.0 / 127.0 / l, rel=1e-6)
+    assert o[1, 0] == pytest.approx(581.0 / 127.0 / l, rel=1e-6)
+
+
+def test_whole_path_visits_a_mask_rows_ascending_hand_worked():
+    # the same case through the bitmask -> block list -> attention path: the list made from a mask is ascending
+    q, sq, k, sk, v, sv = _order_case()
+    bits = np.array([[0b0011]], np.uint8)  # row block 0 attends column blocks 0 and 1 (k = 2: bits 0 and 1)
+    rp, ci = po.mask_to_blocklist(bits, 1, 2)
+    assert ci.tolist() == [0, 1]
+    o = po.sparse_attention_head(q, sq, k, sk, v, sv, 4, 2, rp[0], ci, 127)
+    assert o[0, 0] == pytest.approx(343.0 / 127.0 / (25.0 / 16.0), rel=1e-6)
+    assert o[1, 0] == pytest.approx(580.5 / 127.0 / (25.0 / 16.0), rel=1e-6)
+
+
+def test_tie_risk_bounds_the_effect_of_a_rounding_tie():
     # One 2x2 tile, d = 1, P = [[1, .5], [1, .5]] -> P / sP = [127, 63.5]: a tie.  Rounding the
-    # tie the other way moves the output by exactly sP * |v1| / l, which is what flip_risk reports.
+    # tie the other way moves the output by exactly sP * |v1| / l, which is what the test-side
+    # observer reports.
+    from tests.helpers import TieRisk
+
     n, block = 2, 2
     q = np.ones((2, 1))
     k = np.array([[0.0], [-math.log(2.0)]])
     v = np.array([[3.0], [-5.0]])
     ones = np.ones(1, np.float32)
     rp, ci = np.array([0, 1], np.int32), np.array([0], np.int32)
-    diag = {}
-    o = po.sparse_attention_head(q, ones, k, ones, v, ones, n, block, rp, ci, 127, tie_tol=1e-9, diag=diag)
+    risk = TieRisk(v, ones, block, n, 1e-9)
+    o = po.sparse_attention_head(q, ones, k, ones, v, ones, n, block, rp, ci, 127, observer=risk)
+    assert np.array_equal(o, po.sparse_attention_head(q, ones, k, ones, v, ones, n, block, rp, ci, 127))  # observing changes nothing
     l = 1.5
     up = (127 * 3.0 + 64 * -5.0) / 127 / l
     down = (127 * 3.0 + 63 * -5.0) / 127 / l
     assert np.allclose(o[:, 0], up, rtol=1e-12) or np.allclose(o[:, 0], down, rtol=1e-12)
-    assert np.allclose(diag["flip_risk"][:, 0], 5.0 / 127 / l, rtol=1e-12)
-    assert abs(up - down) <= diag["flip_risk"][0, 0] * (1 + 1e-12)
+    assert np.allclose(risk.out[:, 0], 5.0 / 127 / l, rtol=1e-12)
+    assert abs(up - down) <= risk.out[0, 0] * (1 + 1e-12)
     # away from ties nothing is flagged
-    diag2 = {}
+    risk2 = TieRisk(v, ones, block, n, 1e-9)
     k2 = np.array([[0.0], [-0.3]])
-    po.sparse_attention_head(q, ones, k2, ones, v, ones, n, block, rp, ci, 127, tie_tol=1e-9, diag=diag2)
-    assert np.all(diag2["flip_risk"] == 0)
+    po.sparse_attention_head(q, ones, k2, ones, v, ones, n, block, rp, ci, 127, observer=risk2)
+    assert np.all(risk2.out == 0)
 
 
 def test_bf16_mode_rounds_operands_only():
