@@ -52,22 +52,6 @@ def recorded_valu_instructions(workload: str):
         return None
 
 
-def sustained_mfma_rate(pb, torch, bits):
-    """TOP/s (or TFLOP/s) of a kernel that only issues dense matrix instructions: the rate this GPU
-    sustains, as opposed to the published peak."""
-    out = torch.empty(4096, dtype=torch.int32, device="cuda:0")
-    for _ in range(3):
-        pb.paro_probe_mfma(bits, 4000, out)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    ops = 0
-    for _ in range(10):
-        ops += pb.paro_probe_mfma(bits, 4000, out)
-    e1.record()
-    torch.cuda.synchronize()
-    return ops / (e0.elapsed_time(e1) * 1e-3) / 1e12
-
-
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -328,7 +312,9 @@ def main():
     algorithmic_bytes = int(w.B * w.nh * w.npad * w.d * (2 * qk_bytes + v_bytes) + w.B * w.nh * w.N * w.d * (2 if w.dtype == "bf16" else 4))
     peak = PEAK_INT8_TOPS if quantized else PEAK_BF16_TFLOPS
     achieved = live_ops / (attn_avg * 1e-3) / 1e12
-    sustained = sustained_mfma_rate(pb, torch, 8 if quantized else 16)
+    from paper_2506_16054_amd import probe
+
+    sustained = probe.sustained_mfma_rate(8 if quantized else 16)
     valu = recorded_valu_instructions(w.name) if quantized else None
     out = {
         "metric": "dense_equivalent_TOPS",

@@ -104,6 +104,20 @@ int paro_vt_slot(int block, int i);
 int paro_mask_to_blocklist(int nh, int k, const uint8_t* h_bitmask, int32_t* h_row_ptr,
                            int32_t* h_col_idx, int64_t cap, int64_t* nnz_out);
 
+/* Checks a caller-made block list against what the attention kernels assume (they clamp, they do
+ * not check): per head and row block the offsets are an ascending range inside [0, nnz], and the
+ * column blocks of a row lie in [0, k) and are strictly ascending - the visiting order of the
+ * method (Sec. 4.3 (1),(2): P is quantized per visit, so the order is part of the result), and
+ * what lets the kernels treat the ragged last column block as the last entry of its row.
+ * Lists made by paro_mask_to_blocklist(_device) satisfy it by construction.  Host pointers.
+ * Returns PARO_OK or PARO_EINVAL with the first offending entry in paro_last_error(). */
+int paro_check_blocklist(int nh, int k, const int32_t* h_row_ptr, const int32_t* h_col_idx, int64_t nnz);
+
+/* Checks that h_order [B*nh*k] (host) is a permutation of the row blocks 0 .. B*nh*k - 1: a launch
+ * order that names a row block twice leaves another one unwritten.  paro_schedule_rows' output
+ * satisfies it by construction. */
+int paro_check_row_order(const paro_shape* s, const int32_t* h_order);
+
 /* Launch order of the row blocks for paro_sparse_attn (a performance hint, never a change of
  * results).  Rows of a static mask differ widely in live blocks (Sec. 4.2 (3): one threshold per
  * head), so the kernels can start the heaviest row blocks first.  h_order has B*nh*k entries;
@@ -161,7 +175,9 @@ int paro_quantize(const paro_shape* s, paro_dtype dtype, int bits, paro_layout l
  *   sq,sk,sv float32 [B,nh,k] (ignored, may be NULL, when the operand is 16-bit)
  *   row_ptr  int32 [nh][k+1], col_idx int32 [nnz]: DEVICE copies of the block list; entries
  *            outside [0,nnz] / [0,k) are clamped, so a corrupt list cannot address outside the
- *            operands (the result is then meaningless but the call is memory-safe)
+ *            operands (the result is then meaningless but the call is memory-safe).  The columns
+ *            of a row must be strictly ascending (paro_check_blocklist on the host copy verifies
+ *            a list that did not come from paro_mask_to_blocklist)
  *   row_order int32 [B*nh*k], DEVICE copy of paro_schedule_rows' output, or NULL for the natural
  *            order; must be a permutation of 0..B*nh*k-1 (entries are clamped; a row block that
  *            is missing from it is not computed, one that appears twice is computed twice)
@@ -303,15 +319,6 @@ int paro_calib_choose(int nh, const float* m_sparse6, const float* m_quant6, flo
  *   bitmask    uint8 [nh][ceil(k*k/8)] (out), layout as paro_mask_to_blocklist */
 int paro_calib_mask(const paro_shape* s, const float* block_sum, float density, uint8_t* bitmask,
                     void* stream);
-
-/* ---- measurement aid ------------------------------------------------------------------------
- * Enqueues a kernel that does nothing but issue dense matrix instructions on register operands
- * (four wavefronts per SIMD on 256 compute units, `iters` rounds of four independent
- * v_mfma_i32_32x32x32_i8 (bits 8) or v_mfma_f32_32x32x16_bf16 (bits 16) each) and returns the
- * number of operations (2 per multiply-add) it performs, or a negative status.  Timed by the
- * caller, it gives the matrix rate this GPU sustains, to quote beside the published peak.
- *   out  int32 [out_len], out_len >= 4096: one checksum per wavefront (keeps the work alive) */
-int64_t paro_probe_mfma(int bits, int iters, int32_t* out, int64_t out_len, void* stream);
 
 #ifdef __cplusplus
 }

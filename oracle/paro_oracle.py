@@ -207,9 +207,10 @@ def sparse_attention_head(
     running row maxima the result depends on that order (Sec. 4.3 (1),(2)).
 
     ``observer``, if given, is shown the intermediate quantities and changes nothing:
-    ``observer.visit(i, j, p, codes, s_p, alpha)`` after every visited block (P tile, its integer
-    codes and scale - None when P is not quantized - and the rescale factor of the earlier sums)
-    and ``observer.row_block_done(i, l)`` with the final denominators of row block i.
+    ``observer.visit(i, j, x, m_new, p, codes, s_p, alpha)`` after every visited block (logits, new
+    row maxima, P tile, its integer codes and scale - None when P is not quantized - and the rescale
+    factor of the earlier sums) and ``observer.row_block_done(i, l)`` with the final denominators of
+    row block i.
     """
     npad, d = qc.shape
     k = npad // block
@@ -249,7 +250,7 @@ def sparse_attention_head(
             acc = alpha[:, None] * acc + pv
             m = m_new
             if observer is not None:
-                observer.visit(i, j, p, codes, s_p, alpha)
+                observer.visit(i, j, x, m_new, p, codes, s_p, alpha)
         nz = l > 0
         out[r0 : r0 + n_rows][nz] = acc[nz] / l[nz, None]
         if observer is not None:

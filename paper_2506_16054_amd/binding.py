@@ -27,9 +27,9 @@ LIBPATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libpa
 EXPORTS = (
     "paro_version", "paro_strerror", "paro_last_error", "paro_ntokens", "paro_nblocks", "paro_npad",
     "paro_perm_index", "paro_vt_slot", "paro_mask_to_blocklist", "paro_permute", "paro_unpermute",
-    "paro_quantize", "paro_sparse_attn", "paro_permute_quantize", "paro_sparse_attn_unpermuted", "paro_schedule_rows",
+    "paro_quantize", "paro_sparse_attn", "paro_permute_quantize", "paro_sparse_attn_unpermuted", "paro_schedule_rows", "paro_check_blocklist", "paro_check_row_order",
     "paro_mask_to_blocklist_device", "paro_calib_block_stats", "paro_calib_metrics", "paro_calib_choose", "paro_calib_mask",
-    "paro_probe_mfma", "paro_sparse_attn_unpermuted_rawq", "paro_blocklist_cols_device", "paro_permute_quantize_qkv",
+    "paro_sparse_attn_unpermuted_rawq", "paro_blocklist_cols_device", "paro_permute_quantize_qkv",
 )
 
 
@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.paro_quantize.argtypes = [sp, i32, i32, i32, vp, vp, vp, vp]
         L.paro_sparse_attn.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, i32, vp, vp]
         L.paro_schedule_rows.argtypes = [sp, i32, i32, vp, vp]
+        L.paro_check_blocklist.argtypes = [i32, i32, vp, vp, i64]
+        L.paro_check_row_order.argtypes = [sp, vp]
         L.paro_permute_quantize.argtypes = [sp, i32, i32, i32, vp, vp, vp, vp, vp]
         L.paro_sparse_attn_unpermuted.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i32, vp, vp]
         L.paro_mask_to_blocklist_device.argtypes = [i32, i32, vp, vp, vp, i64, vp, vp]
@@ -81,8 +83,6 @@ def lib() -> ctypes.CDLL:
         L.paro_sparse_attn_unpermuted_rawq.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i32, vp, vp]
         L.paro_blocklist_cols_device.argtypes = [i32, i32, vp, vp, vp, i64, vp]
         L.paro_permute_quantize_qkv.argtypes = [sp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
-        L.paro_probe_mfma.restype = i64
-        L.paro_probe_mfma.argtypes = [i32, i32, vp, i64, vp]
         _lib = L
     return _lib
 
@@ -185,6 +185,24 @@ def paro_mask_to_blocklist(nh: int, k: int, bitmask: np.ndarray) -> Tuple[np.nda
     col_idx = np.empty(max(nnz.value, 1), np.int32)
     _check(lib().paro_mask_to_blocklist(nh, k, bm.ctypes.data, row_ptr.ctypes.data, col_idx.ctypes.data, col_idx.size, ctypes.byref(nnz)))
     return row_ptr, col_idx[: nnz.value]
+
+
+def paro_check_blocklist(nh: int, k: int, row_ptr: np.ndarray, col_idx: np.ndarray) -> None:
+    """Raises ParoError unless the host block list is what the attention kernels assume."""
+    rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    ci = np.ascontiguousarray(col_idx, dtype=np.int32)
+    if rp.shape != (nh, k + 1):
+        raise ParoError(PARO_EINVAL, "row_ptr has shape %s, expected (%d, %d)" % (rp.shape, nh, k + 1))
+    _check(lib().paro_check_blocklist(int(nh), int(k), rp.ctypes.data, ci.ctypes.data if ci.size else None, int(ci.size)))
+
+
+def paro_check_row_order(s: paro_shape, row_order: np.ndarray) -> None:
+    """Raises ParoError unless the host launch order is a permutation of all row blocks."""
+    ro = np.ascontiguousarray(row_order, dtype=np.int32)
+    total = s.B * s.nh * paro_nblocks(s)
+    if ro.shape != (total,):
+        raise ParoError(PARO_EINVAL, "row_order has shape %s, expected (%d,)" % (ro.shape, total))
+    _check(lib().paro_check_row_order(ctypes.byref(s), ro.ctypes.data))
 
 
 def paro_schedule_rows(s: paro_shape, bits_qk: int, bits_pv: int, row_ptr: np.ndarray) -> np.ndarray:
@@ -337,17 +355,6 @@ def paro_calib_mask(s: paro_shape, block_sum, density: float, bitmask) -> None:
     _require(block_sum, "block_sum", (s.B, s.nh, kb, kb), torch.float32)
     _require(bitmask, "bitmask", (s.nh, (kb * kb + 7) // 8), torch.uint8)
     _check(lib().paro_calib_mask(ctypes.byref(s), _ptr(block_sum), float(density), _ptr(bitmask), _stream()))
-
-
-def paro_probe_mfma(bits: int, iters: int, out) -> int:
-    """Enqueues the matrix-rate probe; returns the number of operations it performs."""
-    import torch
-
-    _require(out, "out", None, torch.int32)
-    ops = lib().paro_probe_mfma(int(bits), int(iters), _ptr(out), int(out.numel()), _stream())
-    if ops < 0:
-        _check(int(ops))
-    return int(ops)
 
 
 def _attn_operands(s: paro_shape, bits_qk: int, bits_pv: int, q, sq, k, sk, v, sv, row_ptr, col_idx) -> None:

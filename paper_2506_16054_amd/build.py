@@ -1,4 +1,7 @@
-"""Compiles the HIP sources under csrc/ into lib/libparo.so for gfx950 (in-tree, no JIT cache).
+"""Compiles the HIP sources under csrc/ for gfx950, in-tree (no JIT cache):
+
+    lib/libparo.so        the product library (everything include/paro.h declares)
+    lib/libparo_probe.so  measurement aids of bench.py (csrc/probe/): matrix-rate and instruction-issue probes
 
     python -m paper_2506_16054_amd.build
 """
@@ -15,7 +18,9 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIBDIR = os.path.join(PKG, "lib")
 LIBPATH = os.path.join(LIBDIR, "libparo.so")
-SOURCES = ("host_api.cpp", "permute.hip", "quantize.hip", "blocklist.hip", "calibrate.hip", "probe.hip", "sparse_attn.hip")
+PROBE_LIBPATH = os.path.join(LIBDIR, "libparo_probe.so")
+SOURCES = ("host_api.cpp", "permute.hip", "quantize.hip", "blocklist.hip", "calibrate.hip", "sparse_attn.hip")
+PROBE_SOURCES = ("probe/issue_probe.hip",)
 
 # -packed-fp32-ops is switched off on purpose: all float math here is scalar per lane.
 HIPCC_FLAGS = [
@@ -48,7 +53,7 @@ def spilling_kernels(remarks: str):
 
 
 def _compile(src: str, extra, objdir: str = LIBDIR) -> str:
-    obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
+    obj = os.path.join(objdir, os.path.splitext(os.path.basename(src))[0] + ".o")
     device = src.endswith(".hip")
     report = ["-Rpass-analysis=kernel-resource-usage"] if device else []
     cmd = [hipcc(), *HIPCC_FLAGS, *report, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
@@ -63,18 +68,27 @@ def _compile(src: str, extra, objdir: str = LIBDIR) -> str:
     return obj
 
 
-def build_library(extra_flags=(), verbose: bool = True, out: str = LIBPATH) -> str:
-    """Compile every source and link ``out`` (default: the in-tree library the binding loads)."""
-    objdir = os.path.dirname(out)
-    os.makedirs(objdir, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as ex:
-        objs = list(ex.map(lambda s: _compile(s, list(extra_flags), objdir), SOURCES))
+def _link(out: str, objs) -> None:
     cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
+
+
+def build_library(extra_flags=(), verbose: bool = True, out: str = LIBPATH, probe_out: str | None = PROBE_LIBPATH) -> str:
+    """Compile every source and link ``out`` (default: the in-tree library the binding loads) and, unless
+    ``probe_out`` is None, the measurement-aid library next to it."""
+    objdir = os.path.dirname(out)
+    os.makedirs(objdir, exist_ok=True)
+    srcs = SOURCES + (PROBE_SOURCES if probe_out else ())
+    with ThreadPoolExecutor(max_workers=4) as ex:
+        objs = list(ex.map(lambda s: _compile(s, list(extra_flags), objdir), srcs))
+    _link(out, objs[: len(SOURCES)])
+    if probe_out:
+        os.makedirs(os.path.dirname(probe_out), exist_ok=True)
+        _link(probe_out, objs[len(SOURCES):])
     if verbose:
-        print("built", out)
+        print("built", out, probe_out or "")
     return out
 
 

@@ -162,6 +162,45 @@ int paro_mask_to_blocklist(int nh, int k, const uint8_t* h_bitmask, int32_t* h_r
     return PARO_OK;
 }
 
+int paro_check_blocklist(int nh, int k, const int32_t* h_row_ptr, const int32_t* h_col_idx, int64_t nnz) {
+    if (nh < 1 || k < 1) return fail(PARO_EINVAL, "nh=%d k=%d must be >= 1", nh, k);
+    if (!h_row_ptr) return fail(PARO_EINVAL, "h_row_ptr is NULL");
+    if (nnz < 0 || nnz > 0x7fffffffLL) return fail(PARO_EINVAL, "nnz=%lld out of range", (long long)nnz);
+    if (nnz > 0 && !h_col_idx) return fail(PARO_EINVAL, "h_col_idx is NULL but nnz=%lld", (long long)nnz);
+    for (int h = 0; h < nh; ++h) {
+        const int32_t* rp = h_row_ptr + (int64_t)h * (k + 1);
+        for (int i = 0; i < k; ++i) {
+            const int64_t beg = rp[i], end = rp[i + 1];
+            if (beg < 0 || end < beg || end > nnz)
+                return fail(PARO_EINVAL, "head %d row block %d: offsets [%lld, %lld) are not an ascending range inside [0, %lld]", h, i,
+                            (long long)beg, (long long)end, (long long)nnz);
+            if (end - beg > k) return fail(PARO_EINVAL, "head %d row block %d lists %lld blocks, more than k=%d", h, i, (long long)(end - beg), k);
+            for (int64_t t = beg; t < end; ++t) {
+                const int32_t j = h_col_idx[t];
+                if (j < 0 || j >= k) return fail(PARO_EINVAL, "head %d row block %d: column block %d outside [0, %d)", h, i, j, k);
+                if (t > beg && j <= h_col_idx[t - 1])
+                    return fail(PARO_EINVAL, "head %d row block %d: column blocks %d, %d are not strictly ascending", h, i, h_col_idx[t - 1], j);
+            }
+        }
+    }
+    return PARO_OK;
+}
+
+int paro_check_row_order(const paro_shape* s, const int32_t* h_order) {
+    int64_t n, k;
+    if (int st = check_shape(s, &n, &k)) return st;
+    if (!h_order) return fail(PARO_EINVAL, "h_order is NULL");
+    const int64_t total = (int64_t)s->B * s->nh * k;
+    std::vector<uint8_t> seen((size_t)total, 0);
+    for (int64_t p = 0; p < total; ++p) {
+        const int64_t id = h_order[p];
+        if (id < 0 || id >= total) return fail(PARO_EINVAL, "launch position %lld names row block %lld outside [0, %lld)", (long long)p, (long long)id, (long long)total);
+        if (seen[(size_t)id]) return fail(PARO_EINVAL, "row block %lld appears twice in the launch order (second time at position %lld)", (long long)id, (long long)p);
+        seen[(size_t)id] = 1;
+    }
+    return PARO_OK;
+}
+
 int paro_schedule_rows(const paro_shape* s, int bits_qk, int bits_pv, const int32_t* h_row_ptr, int32_t* h_order) {
     int64_t n, k;
     if (int st = check_shape(s, &n, &k)) return st;

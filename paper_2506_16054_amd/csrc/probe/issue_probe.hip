@@ -1,0 +1,420 @@
+// Measurement aids for bench.py (built into lib/libparo_probe.so, NOT into the product library):
+//
+//   paro_probe_mfma   the matrix-instruction rate this GPU sustains (register operands, no memory);
+//   paro_probe_issue  what one wavefront instruction of a given kind costs a SIMD, in shader-clock
+//                     cycles, with 1..4 wavefronts resident per SIMD, alone or next to a wavefront
+//                     that issues matrix instructions back to back;
+//   paro_probe_block  a register-only replica of the vector-ALU and matrix work of ONE live block of
+//                     the INT8 attention kernel (no global memory, LDS or barrier), to tell issue
+//                     cost from memory and synchronisation cost.
+//
+// Occupancy is set by the launch, without any call that changes a kernel's attributes: a workgroup of
+// 256 threads puts one wavefront on each SIMD of its compute unit and asks for so much LDS (64, 48 or
+// 36 KB of the unit's 160 KB) that exactly W = 2, 3 or 4 workgroups fit, and the grid holds W workgroups
+// per unit, so all are resident at once with W wavefronts per SIMD.  The runs with a matrix companion
+// use one workgroup of 1024 threads per unit (three timed wavefronts and one companion per SIMD; the
+// kernel's register count keeps a second such workgroup out).  Every wavefront records the shader-clock
+// cycles (s_memtime) and the constant 100 MHz ticks it took.  Instruction streams are written as
+// inline assembly on independent registers so that exactly the named instruction is timed; the
+// values computed are meaningless.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kErrInval = -1;
+constexpr int kErrHip = -3;
+char g_error[256] = "";  // text of the last failure (single-threaded measurement tool)
+
+int hip_failed(const char* what, hipError_t e) {
+    snprintf(g_error, sizeof(g_error), "%s: %s", what, hipGetErrorString(e));
+    return kErrHip;
+}
+// LDS request that lets exactly w workgroups share a compute unit's 160 KB
+constexpr int lds_for(int w) { return w == 2 ? 64 * 1024 : w == 3 ? 48 * 1024 : 36 * 1024; }
+constexpr int kUnroll = 32;           // instructions of the timed kind per loop iteration
+
+// ---- the matrix-rate probe --------------------------------------------------------------------
+constexpr int kProbeGroups = 1024;  // workgroups of 256 threads: 4096 wavefronts = 4 per SIMD on 256 CUs
+
+template <int KIND>
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int seed, int* __restrict__ out) {
+    int result = 0;
+    if constexpr (KIND == 0) {
+        v4i a = {seed, 1, 2, 3}, b = {4, 5, 6, seed};
+        v16i c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+        for (int i = 0; i < iters; ++i) {
+            c0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c0, 0, 0, 0);
+            c1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c1, 0, 0, 0);
+            c2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c2, 0, 0, 0);
+            c3 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c3, 0, 0, 0);
+        }
+        for (int r = 0; r < 16; ++r) result += c0[r] + c1[r] + c2[r] + c3[r];
+    } else {
+        v8bf a, b;
+        for (int r = 0; r < 8; ++r) {
+            a[r] = (__bf16)(float)(seed + r);
+            b[r] = (__bf16)(float)(r - seed);
+        }
+        v16f c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+        for (int i = 0; i < iters; ++i) {
+            c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+            c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+            c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+            c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+        }
+        for (int r = 0; r < 16; ++r) result += (int)(c0[r] + c1[r] + c2[r] + c3[r]);
+    }
+    if ((threadIdx.x & 63) == 0) out[blockIdx.x * 4 + (threadIdx.x >> 6)] = result;
+}
+
+// ---- one instruction kind, W wavefronts per SIMD ---------------------------------------------
+enum Kind {
+    K_FMA_F32 = 0, K_ADD_F32, K_MUL_F32, K_MAX3_I32, K_CVT_PKNORM_U16, K_PERM_B32, K_EXP_F32, K_CVT_F32_I32,
+    K_PK_FMA_F16, K_PK_ADD_F16, K_EXP_F16, K_FMA_MIXLO_F16, K_DOT2_F32_F16, K_CVT_PKRTZ_F16, K_MOV_DPP, K_PERMLANE32_SWAP,
+    K_CNDMASK, K_ADD_U32, K_LSHL_OR, K_MFMA_I8_32, K_MFMA_I8_16, K_SOFTMAX_MIX, K_COUNT
+};
+
+const char* const kKindNames[K_COUNT] = {
+    "v_fma_f32", "v_add_f32", "v_mul_f32", "v_max3_i32", "v_cvt_pknorm_u16_f32", "v_perm_b32", "v_exp_f32", "v_cvt_f32_i32",
+    "v_pk_fma_f16", "v_pk_add_f16", "v_exp_f16", "v_fma_mixlo_f16", "v_dot2_f32_f16", "v_cvt_pkrtz_f16_f32", "v_mov_b32 dpp quad_perm",
+    "v_permlane32_swap_b32", "v_cndmask_b32", "v_add_u32", "v_lshl_or_b32", "v_mfma_i32_32x32x32_i8", "v_mfma_i32_16x16x64_i8",
+    "softmax mix (fma, exp, add, 1/2 cvt_pknorm, 1/4 perm, 1/2 max3)"};
+
+#define PROBE_REP8(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7)
+
+// One loop iteration = kUnroll (32) instructions of the kind on 8 independent destination registers.
+template <int KIND>
+__device__ inline void issue_body(float (&f)[8], int (&n)[8], float a, float b, v16i (&acc)[4], v4i ma, v4i mb) {
+#define FMA(i) asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(f[i]) : "v"(a), "v"(b));
+#define ADD(i) asm volatile("v_add_f32 %0, %0, %1" : "+v"(f[i]) : "v"(a));
+#define MUL(i) asm volatile("v_mul_f32 %0, %0, %1" : "+v"(f[i]) : "v"(a));
+#define MAX3(i) asm volatile("v_max3_i32 %0, %0, %1, %2" : "+v"(n[i]) : "v"(n[(i + 1) & 7]), "v"(n[(i + 2) & 7]));
+#define PKN(i) asm volatile("v_cvt_pknorm_u16_f32 %0, %1, %2" : "=v"(n[i]) : "v"(f[i]), "v"(f[(i + 1) & 7]));
+#define PERM(i) asm volatile("v_perm_b32 %0, %0, %1, %2" : "+v"(n[i]) : "v"(n[(i + 1) & 7]), "v"(n[(i + 2) & 7]));
+#define EXP(i) asm volatile("v_exp_f32 %0, %0" : "+v"(f[i]));
+#define CVTI(i) asm volatile("v_cvt_f32_i32 %0, %1" : "=v"(f[i]) : "v"(n[i]));
+#define PKFMA(i) asm volatile("v_pk_fma_f16 %0, %0, %1, %2" : "+v"(f[i]) : "v"(a), "v"(b));
+#define PKADD(i) asm volatile("v_pk_add_f16 %0, %0, %1" : "+v"(f[i]) : "v"(a));
+#define EXP16(i) asm volatile("v_exp_f16 %0, %0" : "+v"(f[i]));
+#define MIXLO(i) asm volatile("v_fma_mixlo_f16 %0, %1, %2, %3" : "+v"(f[i]) : "v"(f[(i + 1) & 7]), "v"(a), "v"(b));
+#define DOT2(i) asm volatile("v_dot2_f32_f16 %0, %1, %2, %0" : "+v"(f[i]) : "v"(a), "v"(b));
+#define PKRTZ(i) asm volatile("v_cvt_pkrtz_f16_f32 %0, %1, %2" : "=v"(n[i]) : "v"(f[i]), "v"(f[(i + 1) & 7]));
+#define DPP(i) asm volatile("v_mov_b32_dpp %0, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf" : "+v"(n[i]) : "v"(n[(i + 1) & 7]));
+#define SWAP(i) asm volatile("v_permlane32_swap_b32 %0, %1" : "+v"(n[i]), "+v"(n[(i + 1) & 7]));
+#define CNDM(i) asm volatile("v_cndmask_b32 %0, %0, %1, vcc" : "+v"(n[i]) : "v"(n[(i + 1) & 7]) : "vcc");
+#define ADDU(i) asm volatile("v_add_u32 %0, %0, %1" : "+v"(n[i]) : "v"(n[(i + 1) & 7]));
+#define LSHLOR(i) asm volatile("v_lshl_or_b32 %0, %0, 8, %1" : "+v"(n[i]) : "v"(n[(i + 1) & 7]));
+#define FOUR(M) PROBE_REP8(M) PROBE_REP8(M) PROBE_REP8(M) PROBE_REP8(M)
+    if constexpr (KIND == K_FMA_F32) { FOUR(FMA) }
+    else if constexpr (KIND == K_ADD_F32) { FOUR(ADD) }
+    else if constexpr (KIND == K_MUL_F32) { FOUR(MUL) }
+    else if constexpr (KIND == K_MAX3_I32) { FOUR(MAX3) }
+    else if constexpr (KIND == K_CVT_PKNORM_U16) { FOUR(PKN) }
+    else if constexpr (KIND == K_PERM_B32) { FOUR(PERM) }
+    else if constexpr (KIND == K_EXP_F32) { FOUR(EXP) }
+    else if constexpr (KIND == K_CVT_F32_I32) { FOUR(CVTI) }
+    else if constexpr (KIND == K_PK_FMA_F16) { FOUR(PKFMA) }
+    else if constexpr (KIND == K_PK_ADD_F16) { FOUR(PKADD) }
+    else if constexpr (KIND == K_EXP_F16) { FOUR(EXP16) }
+    else if constexpr (KIND == K_FMA_MIXLO_F16) { FOUR(MIXLO) }
+    else if constexpr (KIND == K_DOT2_F32_F16) { FOUR(DOT2) }
+    else if constexpr (KIND == K_CVT_PKRTZ_F16) { FOUR(PKRTZ) }
+    else if constexpr (KIND == K_MOV_DPP) { FOUR(DPP) }
+    else if constexpr (KIND == K_PERMLANE32_SWAP) { FOUR(SWAP) }
+    else if constexpr (KIND == K_CNDMASK) { FOUR(CNDM) }
+    else if constexpr (KIND == K_ADD_U32) { FOUR(ADDU) }
+    else if constexpr (KIND == K_LSHL_OR) { FOUR(LSHLOR) }
+    else if constexpr (KIND == K_MFMA_I8_32) {
+        // 32 matrix instructions on four independent accumulators
+#pragma unroll
+        for (int r = 0; r < kUnroll; ++r) acc[r & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ma, mb, acc[r & 3], 0, 0, 0);
+    } else if constexpr (KIND == K_MFMA_I8_16) {
+        typedef int v4acc __attribute__((ext_vector_type(4)));
+        v4acc c[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) c[r] = v4acc{acc[r][0], acc[r][1], acc[r][2], acc[r][3]};
+#pragma unroll
+        for (int r = 0; r < kUnroll; ++r) c[r & 3] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ma, mb, c[r & 3], 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { acc[r][0] = c[r][0]; acc[r][1] = c[r][1]; acc[r][2] = c[r][2]; acc[r][3] = c[r][3]; }
+    } else {
+        // the per-logit sequence of the attention kernel, 8 logits per round, 32 instructions:
+        // 8 x (fma, exp, add) + 4 cvt_pknorm + 2 perm + 2 max3  (the last two instructions pad to 32 with max3)
+#define LOGIT(i) FMA(i) EXP(i) asm volatile("v_add_f32 %0, %0, %1" : "+v"(a) : "v"(f[i]));
+        PROBE_REP8(LOGIT)
+        PKN(0) PKN(2) PKN(4) PKN(6)
+        PERM(0) PERM(4)
+        MAX3(1) MAX3(5)
+#undef LOGIT
+    }
+#undef FOUR
+}
+
+struct WaveTimes {
+    long long cycles;  // s_memtime difference: shader-clock cycles
+    long long ticks;   // constant 100 MHz counter difference
+    long long start;   // s_memtime at the start of the timed loop
+    long long where;   // HW_ID register (SIMD, compute unit, shader engine) | XCC_ID << 32
+};
+
+__device__ inline long long where_am_i() {
+    const unsigned hw = __builtin_amdgcn_s_getreg(4 | (31 << 11));    // HW_REG_HW_ID, all 32 bits
+    const unsigned xcc = __builtin_amdgcn_s_getreg(20 | (31 << 11));  // HW_REG_XCC_ID
+    return (long long)hw | ((long long)xcc << 32);
+}
+
+// role of a wavefront in a launch with a matrix companion: with 4 W wavefronts per workgroup, wavefront w
+// runs on SIMD w % 4; the wavefronts with w / 4 == W - 1 (one per SIMD) issue matrix instructions only
+// and keep going until every timed wavefront of the workgroup has finished.
+template <int KIND>
+__global__ __launch_bounds__(1024) void issue_kernel(int iters, int with_mfma, WaveTimes* __restrict__ out, int* __restrict__ sink) {
+    extern __shared__ int lds_flags[];
+    const int wave = threadIdx.x >> 6;
+    const int waves = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63;
+    float f[8];
+    int n[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        f[i] = 0.001f * (float)(lane + i) - 0.5f;
+        n[i] = lane * 7 + i;
+    }
+    v16i acc[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[r][e] = 0;
+    const v4i ma = {lane, 1, 2, 3}, mb = {4, 5, 6, lane};
+    if (threadIdx.x == 0) lds_flags[0] = 0;
+    __syncthreads();
+    const bool companion = with_mfma && wave >= waves - 4;
+    long long c0 = 0, c1 = 0, t0 = 0, t1 = 0;
+    if (companion) {
+        // matrix instructions until the timed wavefronts are done (they count themselves off in LDS);
+        // the bound on the rounds makes the loop end whatever happens
+        const int done_at = waves - 4;
+        for (int round = 0; round < (1 << 22); ++round) {
+            t1 = round + 1;  // rounds of 8 matrix instructions completed by this companion
+#pragma unroll
+            for (int r = 0; r < 8; ++r) acc[r & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ma, mb, acc[r & 3], 0, 0, 0);
+            if (__hip_atomic_load(&lds_flags[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) >= done_at) break;
+        }
+    } else {
+        c0 = __builtin_readcyclecounter();
+        t0 = wall_clock64();
+        for (int i = 0; i < iters; ++i) issue_body<KIND>(f, n, 1.0001f, 0.0003f, acc, ma, mb);
+        c1 = __builtin_readcyclecounter();
+        t1 = wall_clock64();
+        if (lane == 0) __hip_atomic_fetch_add(&lds_flags[0], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    int keep = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) keep += n[i] + (int)f[i];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) keep += acc[r][0] + acc[r][5];
+    if (lane == 0) {
+        out[blockIdx.x * waves + wave] = companion ? WaveTimes{0, t1, 0, where_am_i()} : WaveTimes{c1 - c0, t1 - t0, c0, where_am_i()};
+        sink[blockIdx.x * waves + wave] = keep;
+    }
+}
+
+// ---- replica of one live block of the INT8 attention kernel (d = 64, 32 queries x 64 keys per wavefront) ------
+// Same instruction sequence per block as the product kernel's loop body minus everything that touches memory:
+// 4 + 4 matrix instructions, the integer row maximum, the logit fma + exp2 + row sum, the code conversion and
+// packing, and the accumulator update.  `parts` switches groups of it off to price them in place:
+// bit 0 matrix instructions, bit 1 exp2, bit 2 conversion + packing, bit 3 row maximum, bit 4 accumulator update,
+// bit 5 row sum.
+template <int PARTS>
+__global__ __launch_bounds__(1024) void block_kernel(int iters, WaveTimes* __restrict__ out, int* __restrict__ sink) {
+    const int wave = threadIdx.x >> 6;
+    const int waves = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63;
+    v4i kf = {lane, 2, 3, 4}, qf = {5, 6, 7, lane}, vf = {lane, 9, 1, 2};
+    v16i init;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) init[r] = 0x4B400000;
+    asm volatile("" : "+v"(init));
+    float acc[2][16];
+#pragma unroll
+    for (int d = 0; d < 2; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[d][r] = 0.0f;
+    float m = -1e30f, l = 0.0f;
+    const float c = 3.0e-4f;
+    const long long c0 = __builtin_readcyclecounter();
+    const long long t0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+        v16i s[2];
+#pragma unroll
+        for (int T = 0; T < 2; ++T) {
+            s[T] = init;
+            if constexpr (PARTS & 1) {
+                s[T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf, s[T], 0, 0, 0);
+                s[T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf, s[T], 0, 0, 0);
+            } else {
+                s[T][0] += kf[0] + it;
+            }
+        }
+        int part[4] = {0, 0, 0, 0};
+        if constexpr (PARTS & 8) {
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) part[r & 3] = max(part[r & 3], s[T][r]);
+        } else {
+            part[0] = s[0][0];
+        }
+        const int mx = max(max(part[0], part[1]), max(part[2], part[3]));
+        const float ymax = c * (__int_as_float(mx) - 12582912.0f);
+        m = fmaxf(m, ymax);
+        const float off = -9.0f - m - c * 12582912.0f;
+        float rs = 0.0f;
+        v4i pf[2];
+#pragma unroll
+        for (int T = 0; T < 2; ++T)
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                float ev[4];
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    ev[p] = fmaf(__int_as_float(s[T][4 * qd + p]), c, off);
+                    if constexpr (PARTS & 2) ev[p] = __builtin_amdgcn_exp2f(ev[p]);
+                    if constexpr (PARTS & 32) rs += ev[p];
+                    else if (p == 0 && qd == 0) rs += ev[p];
+                }
+                if constexpr (PARTS & 4) {
+                    const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[0], ev[1]));
+                    const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[2], ev[3]));
+                    pf[T][qd] = (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u);
+                } else {
+                    pf[T][qd] = __float_as_int(ev[0]) ^ __float_as_int(ev[1]) ^ __float_as_int(ev[2]) ^ __float_as_int(ev[3]);
+                }
+            }
+        l = fmaf(rs, 0.5f, l);
+        const float w = 1.0f / (1.0f + l);
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            v16i o = init;
+            if constexpr (PARTS & 1) {
+                o = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf[0], o, 0, 0, 0);
+                o = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf[1], o, 0, 0, 0);
+            } else {
+                o[0] += pf[0][d] ^ pf[1][d + 2];
+                o[5] += pf[0][d + 2] ^ pf[1][d];
+            }
+#pragma unroll
+            for (int r = 0; r < ((PARTS & 16) ? 16 : 1); ++r) acc[d][r] = fmaf(__int_as_float(o[r]) - 12582912.0f, w, acc[d][r]);
+        }
+        kf[1] ^= it;
+    }
+    const long long c1 = __builtin_readcyclecounter();
+    const long long t1 = wall_clock64();
+    float keep = l + m;
+#pragma unroll
+    for (int d = 0; d < 2; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) keep += acc[d][r];
+    if (lane == 0) {
+        out[blockIdx.x * waves + wave] = WaveTimes{c1 - c0, t1 - t0, c0, where_am_i()};
+        sink[blockIdx.x * waves + wave] = (int)keep;
+    }
+}
+
+template <int KIND>
+int launch_issue(int cus, int w, int iters, int with_mfma, WaveTimes* out, int* sink, hipStream_t st) {
+    if (with_mfma)
+        hipLaunchKernelGGL(issue_kernel<KIND>, dim3(cus), dim3(1024), lds_for(2), st, iters, 1, out, sink);
+    else
+        hipLaunchKernelGGL(issue_kernel<KIND>, dim3(cus * w), dim3(256), lds_for(w), st, iters, 0, out, sink);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? 0 : hip_failed("launch of issue_kernel", e);
+}
+
+template <int PARTS>
+int launch_block(int cus, int w, int iters, WaveTimes* out, int* sink, hipStream_t st) {
+    hipLaunchKernelGGL(block_kernel<PARTS>, dim3(cus * w), dim3(256), lds_for(w), st, iters, out, sink);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? 0 : hip_failed("launch of block_kernel", e);
+}
+
+}  // namespace
+
+extern "C" {
+
+// Matrix-rate probe: `iters` rounds of four independent v_mfma_i32_32x32x32_i8 (bits 8) or
+// v_mfma_f32_32x32x16_bf16 (bits 16) per wavefront, four wavefronts per SIMD on 256 compute units.
+// Returns the number of operations performed (2 per multiply-add), or a negative status.
+//   out  int32 [out_len] (device), out_len >= 4096
+int64_t paro_probe_mfma(int bits, int iters, int32_t* out, int64_t out_len, void* stream) {
+    if ((bits != 8 && bits != 16) || iters < 1 || iters > (1 << 20) || !out || out_len < kProbeGroups * 4) return kErrInval;
+    if (bits == 8)
+        hipLaunchKernelGGL(probe_mfma_kernel<0>, dim3(kProbeGroups), dim3(256), 0, (hipStream_t)stream, iters, 1, out);
+    else
+        hipLaunchKernelGGL(probe_mfma_kernel<1>, dim3(kProbeGroups), dim3(256), 0, (hipStream_t)stream, iters, 1, out);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return hip_failed("launch of probe_mfma_kernel", e);
+    const int64_t per_instr = bits == 8 ? 2LL * 32 * 32 * 32 : 2LL * 32 * 32 * 16;
+    return (int64_t)kProbeGroups * 4 * iters * 4 * per_instr;
+}
+
+const char* paro_probe_last_error(void) { return g_error; }
+
+int paro_probe_issue_kinds(void) { return K_COUNT; }
+
+const char* paro_probe_issue_name(int kind) { return kind >= 0 && kind < K_COUNT ? kKindNames[kind] : ""; }
+
+// Enqueues the stream of instruction `kind` with `waves_per_simd` (2..4) wavefronts per SIMD on `cus` compute
+// units (pass the device's count).  with_mfma != 0: waves_per_simd must be 4; three wavefronts per SIMD are
+// timed and the fourth is a companion that issues v_mfma_i32_32x32x32_i8 back to back for as long as they run.
+// Every timed wavefront issues iters * 32 instructions and writes its elapsed {shader cycles, 100 MHz ticks}
+// to times[workgroup * wavefronts per workgroup + wavefront]; a companion writes 0 cycles and, as its ticks, the
+// number of rounds of 8 matrix instructions it got through meanwhile.
+// Returns the number of entries of `times` written, or a negative status.
+//   times  int64 [4 * entries] (device: cycles, ticks, start cycle, placement per wavefront);  sink  int32 [entries] (device, keeps the work alive)
+int paro_probe_issue(int kind, int cus, int waves_per_simd, int iters, int with_mfma, int64_t* times, int32_t* sink, int64_t capacity, void* stream) {
+    if (kind < 0 || kind >= K_COUNT || cus < 1 || cus > 4096 || waves_per_simd < 2 || waves_per_simd > 4 || iters < 1 || iters > (1 << 20) || !times || !sink)
+        return kErrInval;
+    if (with_mfma && waves_per_simd != 4) return kErrInval;
+    const int entries = cus * 4 * waves_per_simd;
+    if (capacity < entries) return kErrInval;
+    hipStream_t st = (hipStream_t)stream;
+    WaveTimes* out = (WaveTimes*)times;
+    int rc = kErrInval;
+    switch (kind) {
+#define CASE(K) case K: rc = launch_issue<K>(cus, waves_per_simd, iters, with_mfma, out, sink, st); break;
+        CASE(K_FMA_F32) CASE(K_ADD_F32) CASE(K_MUL_F32) CASE(K_MAX3_I32) CASE(K_CVT_PKNORM_U16) CASE(K_PERM_B32) CASE(K_EXP_F32)
+        CASE(K_CVT_F32_I32) CASE(K_PK_FMA_F16) CASE(K_PK_ADD_F16) CASE(K_EXP_F16) CASE(K_FMA_MIXLO_F16) CASE(K_DOT2_F32_F16)
+        CASE(K_CVT_PKRTZ_F16) CASE(K_MOV_DPP) CASE(K_PERMLANE32_SWAP) CASE(K_CNDMASK) CASE(K_ADD_U32) CASE(K_LSHL_OR)
+        CASE(K_MFMA_I8_32) CASE(K_MFMA_I8_16) CASE(K_SOFTMAX_MIX)
+#undef CASE
+    }
+    return rc < 0 ? rc : entries;
+}
+
+// Enqueues the register-only replica of one live block of the INT8 attention kernel (see block_kernel),
+// `iters` blocks per wavefront, waves_per_simd (2..4) wavefronts per SIMD on `cus` compute units.
+// parts: 63 = everything; clearing a bit leaves that group of instructions out (bit 0 the 8 matrix
+// instructions, 1 the 32 exp2, 2 conversion + packing, 3 the row maximum, 4 the accumulator update, 5 the row sum).
+// Supported values of parts: 63, 62, 61, 59, 55, 47, 31, 0.  Output as paro_probe_issue.
+int paro_probe_block(int parts, int cus, int waves_per_simd, int iters, int64_t* times, int32_t* sink, int64_t capacity, void* stream) {
+    if (cus < 1 || cus > 4096 || waves_per_simd < 2 || waves_per_simd > 4 || iters < 1 || iters > (1 << 20) || !times || !sink) return kErrInval;
+    const int entries = cus * 4 * waves_per_simd;
+    if (capacity < entries) return kErrInval;
+    hipStream_t st = (hipStream_t)stream;
+    WaveTimes* out = (WaveTimes*)times;
+    int rc = kErrInval;
+    switch (parts) {
+#define CASE(P) case P: rc = launch_block<P>(cus, waves_per_simd, iters, out, sink, st); break;
+        CASE(63) CASE(62) CASE(61) CASE(59) CASE(55) CASE(47) CASE(31) CASE(0)
+#undef CASE
+    }
+    return rc < 0 ? rc : entries;
+}
+
+}  // extern "C"

@@ -23,7 +23,12 @@
 // Arithmetic per live block (X in log2 units, c = sq_i * sk_j * log2(e) / sqrt(d)):
 //   m' = max(m, c * rowmax S)  (the row maximum is taken on the integers, c > 0);  e = max over valid rows of (c * rowmax S - m')   (<= 0)
 //   E  = qmaxP * 2^(c*S - m' - e)  in (0, qmaxP]  ->  Pc = round-half-even(E), two codes per
-//        v_cvt_pknorm_u16_f32 (E is formed pre-divided by 65535), four codes packed by one v_perm_b32,
+//        v_cvt_pknorm_u16_f32 (E is formed pre-divided by 65535), four codes packed by one v_perm_b32.
+//        The exponent is ONE fma on the raw accumulator register: the register read as a float is B + S
+//        (B = 1.5 * 2^23, see int_result), so c*S + off = c*(B + S) + (off - c*B); the offset off - c*B is
+//        rounded to binary32 once per row and block, and that rounding (at most half an ulp of c*B, about
+//        1e-4 relative in E) is computed exactly and returned to the block's weight, so the sums see the
+//        scale the codes were really formed with,
 //   l  = l * 2^(m - m') + sP * rowsum(E),  sP = 2^e / qmaxP   (the P tile maximum over qmaxP)
 //   acc = acc * 2^(m - m') + (sP * sv_j) * float(Pc V_j)
 // The two running sums are held divided by 2^(m' - m_ref), m_ref being the row's maximum after its
@@ -118,14 +123,12 @@ constexpr int kAccBiasI = 0x4B400000;
 constexpr float kAccBiasF = 12582912.0f;
 __device__ inline float int_result(int raw) { return __int_as_float(raw) - kAccBiasF; }
 
-#ifndef PARO_FOLD_S
-#define PARO_FOLD_S 0
-#endif
-#ifndef PARO_ALT_O
-#define PARO_ALT_O 0
-#endif
-#ifndef PARO_ABLATE
-#define PARO_ABLATE 0
+// 1: with 8-bit P codes the accumulator bias of the logits is folded into the offset of the exponent's
+// fma (one vector instruction per logit less); 0: the bias is always subtracted first and the exponent is
+// exact to fp32 rounding.  With 4-bit P codes a code that flips at a rounding tie moves an output element
+// by up to a seventh of its largest term, so that mode always keeps the exact exponent.
+#ifndef PARO_FOLD_LOGIT_BIAS
+#define PARO_FOLD_LOGIT_BIAS 1
 #endif
 #ifndef PARO_ATTN_WAVES_D64
 #define PARO_ATTN_WAVES_D64 3  // wavefronts per SIMD the register allocation must allow, d = 64
@@ -328,9 +331,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 
     float m = -INFINITY;  // running row maximum, log2 units
     float m_ref = -INFINITY;  // the maximum the stored sums are expressed against (set by the first block)
-    constexpr bool ALT_O = PARO_ALT_O && D == 64;
-    constexpr float kLogNorm = ALT_O ? 14.999955971769423f : 15.999977986052736f;  // log2(32767) signed / log2(65535)
-    constexpr float kNorm = ALT_O ? 32767.0f : 65535.0f;
+    constexpr float kLog2_65535 = 15.999977986052736f;
     float w_base = INFINITY;  // -log2(65535) - m_ref
     float l = 0.0f;       // this lane's share of the running denominator, divided by 65535 * 2^(m - m_ref)
     float acc[DT][16];
@@ -344,13 +345,6 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc_init[r] = kAccBiasI;
     asm volatile("" : "+v"(acc_init));  // opaque to the optimizer: not re-created per block
-    v16i acc_init_neg;
-    float bias_sum = 0.0f;  // sum of the biases carried by acc (the same for all of a lane's elements)
-    if constexpr (ALT_O) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc_init_neg[r] = (int)0xCB400000;
-        asm volatile("" : "+v"(acc_init_neg));
-    }
 
     // LDS ring of two stages, one barrier per live block (placed after the row maxima):
     //   K_{t+1} is stored at the top of iteration t  - every wavefront finished reading K_{t-1}
@@ -397,10 +391,9 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     // One live block.  TAIL selects the variant that masks keys past N (only the last column
     // block of a ragged sequence needs it; keeping it out of the common path saves two
     // instructions per logit).
-    auto step = [&](auto tail_tag, auto neg_tag, int t) {
+    auto step = [&](auto tail_tag, auto fold_tag, int t) {
         constexpr bool TAIL = decltype(tail_tag)::value;
-        constexpr bool NEG = decltype(neg_tag)::value;  // odd visits: P codes negated, output bias negative
-        (void)NEG;
+        constexpr bool FOLD = decltype(fold_tag)::value;
         const int next = stage ^ 1;
         if (t + 1 < cnt) lstore_k(next);
 
@@ -416,8 +409,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 const v4i kf = *(const v4i*)(ks + (32 * T + n) * KSTR + 32 * s + 16 * g);
-                if constexpr (!(PARO_ABLATE & 32)) sacc[T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf[s], sacc[T], 0, 0, 0);
-                else sacc[T][s] ^= kf[0] & 0xff;
+                sacc[T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf[s], sacc[T], 0, 0, 0);
             }
         }
         // Raw accumulator value of a masked logit: it loses every maximum (real values carry the
@@ -437,7 +429,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 #pragma unroll
         for (int T = 0; T < KT; ++T)
 #pragma unroll
-            for (int r = 0; r < ((PARO_ABLATE & 4) ? 1 : 16); ++r) part[r & 3] = max(part[r & 3], sacc[T][r]);
+            for (int r = 0; r < 16; ++r) part[r & 3] = max(part[r & 3], sacc[T][r]);
         const float ymax = c * int_result(xor32_max(max(max(part[0], part[1]), max(part[2], part[3]))));
         const float m_new = fmaxf(m, ymax);
         // e = log2 of the largest entry of the Pt tile = max over valid rows of (row maximum of
@@ -472,9 +464,8 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[dt][r] *= down;
-            if constexpr (ALT_O) bias_sum *= down;
             m_ref = m_new;
-            w_base = -kLogNorm - m_new;
+            w_base = -kLog2_65535 - m_new;
         }
         m = m_new;
 
@@ -485,22 +476,23 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
         // nearest 16-bit integer, two values per instruction) yields the codes; one byte permute
         // packs four of them.  The row sum carries the same factor, undone once per row.
         // Exponent offset: X - m' - e + log2(qmaxP) - log2(65535): the tile maximum maps to qmaxP / 65535.
-        const float off_n = (LOG2_QMAXP - kLogNorm) - m_new - e;
+        const float off_n = (LOG2_QMAXP - kLog2_65535) - m_new - e;
         // weight of this block's terms in the stored sums, sP * 2^(m' - m_ref) = 2^(e + m' - m_ref - log2(qmaxP)),
         // written against the offset above: the part that depends on m_ref alone changes only with m_ref
-#if PARO_FOLD_S
-        // c * (B + S) + off_f with off_f = fl(off_n - c*B): the two roundings (of c*B and of the difference) are
-        // recovered exactly (fma residual, two-sum) and returned to the block weight.
-        const float cb_hi = c * kAccBiasF;
-        const float cb_lo = fmaf(c, kAccBiasF, -cb_hi);
-        const float off_f = off_n - cb_hi;
-        const float bb = off_f - off_n;
-        const float terr = (off_n - (off_f - bb)) + (-cb_hi - bb);
-        const float delta = cb_lo - terr;  // E is formed as E_exact * 2^delta
-        const float w_blk = __builtin_amdgcn_exp2f((w_base - off_n) - delta);
-#else
-        const float w_blk = __builtin_amdgcn_exp2f(w_base - off_n);
-#endif
+        float off_f = off_n, w_blk;
+        if constexpr (FOLD) {
+            // c * (B + S) + off_f with off_f = fl(off_n - c*B).  c*B = cb_hi + cb_lo exactly (fma residual) and
+            // off_n - cb_hi = off_f + terr exactly (two-sum), so E comes out as E_exact * 2^delta with
+            // delta = cb_lo - terr known exactly; the block's weight takes the factor 2^-delta.
+            const float cb_hi = c * kAccBiasF;
+            const float cb_lo = fmaf(c, kAccBiasF, -cb_hi);
+            off_f = off_n - cb_hi;
+            const float bb = off_f - off_n;
+            const float terr = (off_n - (off_f - bb)) + (-cb_hi - bb);
+            w_blk = __builtin_amdgcn_exp2f((w_base - off_n) - (cb_lo - terr));
+        } else {
+            w_blk = __builtin_amdgcn_exp2f(w_base - off_n);
+        }
 #pragma unroll
         for (int T = 0; T < KT; ++T) {
 #pragma unroll
@@ -508,33 +500,17 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
                 float ev[4];
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
-#if PARO_FOLD_S
-                    ev[p] = fmaf(__int_as_float(sacc[T][4 * qd + p]), c, off_f);
-#else
-                    ev[p] = fmaf(int_result(sacc[T][4 * qd + p]), c, off_n);
-#endif
-                    if constexpr (!(PARO_ABLATE & 1)) ev[p] = __builtin_amdgcn_exp2f(ev[p]);
+                    ev[p] = __builtin_amdgcn_exp2f(fmaf(FOLD ? __int_as_float(sacc[T][4 * qd + p]) : int_result(sacc[T][4 * qd + p]), c, off_f));
                     if constexpr (TAIL) {
                         if (32 * T + 8 * qd + 4 * g + p >= a.n_tokens - (a.kblocks - 1) * BLK) ev[p] = 0.0f;
                     }
-                    if constexpr (!(PARO_ABLATE & 64)) rs = (T == 0 && qd == 0 && p == 0) ? ev[p] : rs + ev[p];
-                    else if (T == 0 && qd == 0 && p == 0) rs = ev[p];
+                    rs = (T == 0 && qd == 0 && p == 0) ? ev[p] : rs + ev[p];
                 }
                 // (the builtin, not inline assembly: the instruction consumes results of the
                 // transcendental unit, and only instructions the compiler can see get the wait state
                 // that this needs when they follow the exponential directly)
-                unsigned lo, hi;
-                if constexpr ((PARO_ABLATE & 2) != 0) {
-                    pf[T][qd] = __float_as_int(ev[0]) ^ __float_as_int(ev[1]) ^ __float_as_int(ev[2]) ^ __float_as_int(ev[3]);
-                    continue;
-                }
-                if constexpr (ALT_O) {
-                    lo = __builtin_bit_cast(unsigned, NEG ? __builtin_amdgcn_cvt_pknorm_i16(-ev[0], -ev[1]) : __builtin_amdgcn_cvt_pknorm_i16(ev[0], ev[1]));
-                    hi = __builtin_bit_cast(unsigned, NEG ? __builtin_amdgcn_cvt_pknorm_i16(-ev[2], -ev[3]) : __builtin_amdgcn_cvt_pknorm_i16(ev[2], ev[3]));
-                } else {
-                    lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[0], ev[1]));
-                    hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[2], ev[3]));
-                }
+                const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[0], ev[1]));
+                const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[2], ev[3]));
                 pf[T][qd] = (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u);
             }
         }
@@ -544,19 +520,15 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
         const float sv_eff = w_blk * sv_cur * (PVBITS == 4 ? 0.0625f : 1.0f);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-            v16i o = (ALT_O && NEG) ? acc_init_neg : acc_init;
+            v16i o = acc_init;
 #pragma unroll
             for (int T = 0; T < KT; ++T) {
                 const v4i vf = *(const v4i*)(vs + (32 * dt + n) * VSTR + 32 * T + 16 * g);
-                if constexpr (!(PARO_ABLATE & 16)) o = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf[T], o, 0, 0, 0);
-                else o[T] ^= vf[0] & pf[T][0];
+                o = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf[T], o, 0, 0, 0);
             }
-            // ALT_O: the register read as a float is +-B + result: the bias alternates in sign from visit to visit and
-            // is tracked per lane (bias_sum), so the running sums stay near the size of one block's bias
 #pragma unroll
-            for (int r = 0; r < ((PARO_ABLATE & 8) ? 2 : 16); ++r) acc[dt][r] = fmaf(ALT_O ? __int_as_float(o[r]) : int_result(o[r]), sv_eff, acc[dt][r]);
+            for (int r = 0; r < 16; ++r) acc[dt][r] = fmaf(int_result(o[r]), sv_eff, acc[dt][r]);
         }
-        if constexpr (ALT_O) bias_sum = fmaf(NEG ? -kAccBiasF : kAccBiasF, sv_eff, bias_sum);
         sk_cur = sk_next;
         sv_cur = sv_next;
         stage = next;
@@ -566,26 +538,29 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
     // reads the list directly (once per workgroup).
     const bool has_tail = (a.n_tokens % BLK) != 0 && cnt > 0 && min(max(cols[cnt - 1], 0), a.kblocks - 1) == a.kblocks - 1;
     const int cnt_main = has_tail ? cnt - 1 : cnt;
-    if constexpr (ALT_O) {
-        for (int t = 0; t < cnt_main; t += 2) {
-            step(std::false_type{}, std::false_type{}, t);
-            if (t + 1 < cnt_main) step(std::false_type{}, std::true_type{}, t + 1);
-        }
-        if (has_tail) {
-            if ((cnt - 1) & 1) step(std::true_type{}, std::true_type{}, cnt - 1);
-            else step(std::true_type{}, std::false_type{}, cnt - 1);
-        }
+    // The folded form of the exponent is taken where the logit scales of the row block's tiles keep the
+    // rounding of its offset small: c * B < 2^13 for the largest K scale among the live column blocks, i.e.
+    // at most 2^-12 in the exponent.  Row blocks whose inputs have an unusual magnitude take the exact
+    // form.  The decision is the same in every lane of the workgroup (one row block, one list).
+    constexpr bool FOLDABLE = PARO_FOLD_LOGIT_BIAS && PVBITS == 8;
+    bool fold = false;
+    if constexpr (FOLDABLE) {
+        float sk_max = 0.0f;
+        for (int base = 0; base < cnt; base += 64)
+            if (base + lane < cnt) sk_max = fmaxf(sk_max, skp[min(max(cols[base + lane], 0), a.kblocks - 1)]);
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[dt][r] -= bias_sum;
-    } else {
-        for (int t = 0; t < cnt_main; ++t) step(std::false_type{}, std::false_type{}, t);
-        if (has_tail) step(std::true_type{}, std::false_type{}, cnt - 1);
+        for (int off = 32; off >= 1; off >>= 1) sk_max = fmaxf(sk_max, __shfl_xor(sk_max, off));
+        fold = sq_i * sk_max * kAccBiasF < 8192.0f;
     }
+    auto visit_all = [&](auto fold_tag) {
+        for (int t = 0; t < cnt_main; ++t) step(std::false_type{}, fold_tag, t);
+        if (has_tail) step(std::true_type{}, fold_tag, cnt - 1);
+    };
+    if (fold) visit_all(std::bool_constant<FOLDABLE>{});
+    else visit_all(std::false_type{});
 
     // ---- finalize: divide by the denominator, store the row (zeros for padded rows)
-    const float l_tot = (l + __shfl_xor(l, 32)) * kNorm;
+    const float l_tot = (l + __shfl_xor(l, 32)) * 65535.0f;
     const float inv = (row_valid && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
     const long long ooff = out_row_offset<D>(a, bh, h, head_rows, row, row_valid);
     if (ooff >= 0) {
@@ -840,12 +815,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? 3 : 2)) void attn_bf16_kernel(A
 template <int BLK, int D, typename OutT>
 static int launch_bf16_t(const AttnArgs& a, hipStream_t st) {
     constexpr int bytes = Bf16Cfg<BLK, D>::LDS_BYTES;
-    static bool configured = false;  // raising the dynamic LDS limit is a per-function, idempotent setting
-    if (bytes > 48 * 1024 && !configured) {
-        hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_kernel<BLK, D, OutT>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-        if (e != hipSuccess) return fail(PARO_EHIP, "hipFuncSetAttribute(%d bytes of LDS): %s", bytes, hipGetErrorString(e));
-        configured = true;
-    }
+    static_assert(bytes <= 48 * 1024, "beyond 48 KB the launch would have to raise the function's dynamic LDS limit first");
     hipLaunchKernelGGL((attn_bf16_kernel<BLK, D, OutT>), dim3((unsigned)(a.per_xcd * 8)), dim3(BLK * 2), bytes, st, a);
     return PARO_OK;
 }

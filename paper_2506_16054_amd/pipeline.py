@@ -124,17 +124,6 @@ class ParoAttention:
         return self.attend_rawq(q)
 
 
-def shared_mask_index(timestep: int, n_timesteps: int) -> int:
-    """Which stored mask a sampling step uses under timestep-aware mask sharing (paper Sec. 4.2 (1)):
-    every step of the first half of the schedule has its own mask, all later steps reuse one common
-    mask, stored right after them.  A schedule of T steps therefore stores ceil(T/2) + 1 masks per
-    transformer block (T masks if T < 2)."""
-    if n_timesteps < 1 or not 0 <= timestep < n_timesteps:
-        raise ValueError("timestep %d outside a schedule of %d steps" % (timestep, n_timesteps))
-    first_half = (n_timesteps + 1) // 2
-    return timestep if timestep < first_half else min(first_half, n_timesteps - 1)
-
-
 class MaskPrefetcher:
     """Two device slots for the block list of the attention call at hand and of the next one
     (paper Sec. 4.2 (1), App. C "Overhead of Prefetch").  All masks stay in pinned host memory, each as

@@ -1,0 +1,167 @@
+"""ctypes binding of lib/libparo_probe.so, the measurement aids of bench.py (csrc/probe/): the matrix
+rate the GPU sustains, the issue cost of single vector-ALU instructions, and a register-only replica
+of one live block of the INT8 attention kernel.  Not part of the product library; nothing under
+``binding`` or ``pipeline`` loads it.
+
+    python -m paper_2506_16054_amd.probe          # prints the issue-cost table as markdown
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import sys
+
+LIBPATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libparo_probe.so")
+_lib = None
+
+# parts of the block replica that can be left out (paro_probe_block), and their size per wave-block at d = 64
+BLOCK_PARTS = {
+    "all": 63,
+    "without the 8 matrix instructions": 62,
+    "without the 32 exp2": 61,
+    "without conversion + packing (16 cvt_pknorm + 8 perm -> 24 xor)": 59,
+    "without the row maximum (16 max3)": 55,
+    "without the accumulator update (60 of 64 sub/fma)": 47,
+    "without the row sum (31 add)": 31,
+    "logit fma and bookkeeping only": 0,
+}
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        import torch  # noqa: F401  (first: the library must bind to the HIP runtime that torch has loaded)
+
+        if not os.path.exists(LIBPATH):
+            raise RuntimeError("%s is missing: build it with `python -m paper_2506_16054_amd.build`" % LIBPATH)
+        L = ctypes.CDLL(LIBPATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+        L.paro_probe_mfma.restype = i64
+        L.paro_probe_mfma.argtypes = [i32, i32, vp, i64, vp]
+        L.paro_probe_last_error.restype = ctypes.c_char_p
+        L.paro_probe_issue_kinds.restype = i32
+        L.paro_probe_issue_name.restype = ctypes.c_char_p
+        L.paro_probe_issue_name.argtypes = [i32]
+        L.paro_probe_issue.argtypes = [i32, i32, i32, i32, i32, vp, vp, i64, vp]
+        L.paro_probe_block.argtypes = [i32, i32, i32, i32, vp, vp, i64, vp]
+        _lib = L
+    return _lib
+
+
+def _stream() -> int:
+    import torch
+
+    return torch.cuda.current_stream().cuda_stream
+
+
+def compute_units() -> int:
+    import torch
+
+    return int(torch.cuda.get_device_properties(0).multi_processor_count)
+
+
+def kinds():
+    L = lib()
+    return [L.paro_probe_issue_name(k).decode() for k in range(L.paro_probe_issue_kinds())]
+
+
+def sustained_mfma_rate(bits: int) -> float:
+    """TOP/s (bits 8) or TFLOP/s (bits 16) of a kernel that only issues dense matrix instructions."""
+    import torch
+
+    out = torch.empty(4096, dtype=torch.int32, device="cuda:0")
+
+    def launch():
+        ops = lib().paro_probe_mfma(int(bits), 4000, out.data_ptr(), out.numel(), _stream())
+        if ops < 0:
+            raise RuntimeError("paro_probe_mfma failed with status %d: %s" % (ops, lib().paro_probe_last_error().decode()))
+        return ops
+
+    for _ in range(3):
+        launch()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    ops = sum(launch() for _ in range(10))
+    e1.record()
+    torch.cuda.synchronize()
+    return ops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
+def _times(launch, per_wave_work: float, timed_per_simd: int):
+    """Runs ``launch(times, sink, capacity)`` twice (the second run is read).  The SIMD's arbiter serves its
+    oldest wavefront first, so the wavefronts of a SIMD finish one after the other and the LAST one's elapsed
+    cycles are the time the SIMD needed for all of them: cost per unit of work = that / (work per wavefront x
+    timed wavefronts per SIMD).  Returns (cost in shader cycles, clock in GHz, matrix instructions a companion
+    wavefront issued per 1000 cycles meanwhile or None)."""
+    import torch
+
+    cap = 4096 * 4
+    times = torch.zeros((cap, 4), dtype=torch.int64, device="cuda:0")
+    sink = torch.zeros((cap,), dtype=torch.int32, device="cuda:0")
+    n = 0
+    for _ in range(2):
+        times.zero_()
+        n = launch(times.data_ptr(), sink.data_ptr(), cap)
+        if n < 0:
+            raise RuntimeError("probe launch failed with status %d: %s" % (n, lib().paro_probe_last_error().decode()))
+        torch.cuda.synchronize()
+    full = times[:n].cpu().numpy()
+    timed = full[full[:, 0] > 0]
+    comp = full[full[:, 0] == 0]
+    # per SIMD (placement register: XCC, shader engine, array, compute unit, SIMD): the slowest timed wavefront
+    hw = timed[:, 3] & 0xFFFFFFFF
+    simd = ((timed[:, 3] >> 32) & 0xF) << 20 | (hw & 0xFFF0)
+    last = {}
+    count = {}
+    for key, c in zip(simd.tolist(), timed[:, 0].tolist()):
+        last[key] = max(last.get(key, 0), c)
+        count[key] = count.get(key, 0) + 1
+    if set(count.values()) != {timed_per_simd}:
+        raise RuntimeError("expected %d timed wavefronts on every SIMD, found %s" % (timed_per_simd, sorted(set(count.values()))))
+    import numpy as np
+
+    cycles = float(np.median(list(last.values())))
+    ghz = float((timed[:, 0] / (timed[:, 1] * 10.0)).mean())  # ticks of 10 ns
+    mfma_rate = None
+    if len(comp):
+        mfma_rate = float(comp[:, 1].mean()) * 8.0 / cycles * 1000.0
+    return cycles / (per_wave_work * timed_per_simd), ghz, mfma_rate
+
+
+def issue_cost(kind: int, waves_per_simd: int, with_mfma: bool = False, iters: int = 8000):
+    """(shader cycles one wavefront instruction of ``kind`` costs its SIMD, clock in GHz, companion matrix rate)."""
+    timed = waves_per_simd - (1 if with_mfma else 0)
+    return _times(lambda t, s, cap: lib().paro_probe_issue(kind, compute_units(), waves_per_simd, iters, int(with_mfma), t, s, cap, _stream()),
+                  iters * 32.0, timed)
+
+
+def block_cost(parts: int, waves_per_simd: int, iters: int = 1500):
+    """(shader cycles one replica block costs its SIMD, clock in GHz, None)."""
+    return _times(lambda t, s, cap: lib().paro_probe_block(parts, compute_units(), waves_per_simd, iters, t, s, cap, _stream()),
+                  float(iters), waves_per_simd)
+
+
+def issue_table() -> dict:
+    """All measurements behind profiles/valu_issue_costs.md as a dictionary."""
+    names = kinds()
+    single = {name: {w: issue_cost(k, w) for w in (2, 3, 4)} for k, name in enumerate(names)}
+    beside = {name: issue_cost(k, 4, with_mfma=True) for k, name in enumerate(names) if not name.startswith("v_mfma")}
+    blocks = {label: {w: block_cost(parts, w) for w in (2, 3, 4)} for label, parts in BLOCK_PARTS.items()}
+    return {"single": single, "beside_mfma": beside, "block": blocks}
+
+
+def markdown(tab: dict) -> str:
+    out = ["| instruction | cycles at 2 waves/SIMD | 3 | 4 | clock GHz | 3 waves + a wave of matrix instructions: cycles | matrix instructions per 1000 cycles meanwhile (alone: 30.3) |",
+           "|---|---|---|---|---|---|---|"]
+    for name, row in tab["single"].items():
+        b = tab["beside_mfma"].get(name)
+        out.append("| `%s` | %.2f | %.2f | %.2f | %.2f | %s | %s |" % (name, row[2][0], row[3][0], row[4][0], row[3][1],
+                                                                 "%.2f" % b[0] if b else "-", "%.1f" % b[2] if b else "-"))
+    out += ["", "| block replica (cycles per wave-block per SIMD) | 2 waves/SIMD | 3 | 4 | clock GHz |", "|---|---|---|---|---|"]
+    for label, row in tab["block"].items():
+        out.append("| %s | %.0f | %.0f | %.0f | %.2f |" % (label, row[2][0], row[3][0], row[4][0], row[3][1]))
+    return "\n".join(out)
+
+
+if __name__ == "__main__":
+    sys.stdout.write(markdown(issue_table()) + "\n")

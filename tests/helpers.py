@@ -16,32 +16,55 @@ def blocklist_for(w, masks):
 
 
 # Rounding ties of the P codes.  A P code is an integer decision taken on floating-point values
-# (E = Pt / sP): an implementation whose E carries a relative error up to KERNEL_TIE_TOL may round an
-# entry that lies within that error of a half-integer to the other neighbour, and one such flip moves
-# an output element by sP * sv * |Vc| / l of its key - far more than the evaluation error itself.
-# The figure is the error of the HIP kernel's E, derived from its arithmetic: the logit is one fp32
-# fma of exact integers (relative 2^-24 of an exponent of at most ~2^7, i.e. <= 8e-6 * ln 2 in E), the
-# hardware exp2 is accurate to about 1 ulp (1.2e-7), and the offset of that fma (running maximum, tile
-# exponent and the folded accumulator bias, magnitude c * 1.5 * 2^23 <= ~2^13) is rounded to fp32 once
-# (<= 2^-12 / 2 * ln 2 = 8.5e-5 in E).  1e-4 covers the sum.
-KERNEL_TIE_TOL = 1e-4
+# (E = Pt / sP): an implementation whose E carries a relative error may round an entry that lies
+# within that error of a half-integer to the other neighbour, and one such flip moves an output
+# element by sP * sv * |Vc| / l of its key - far more than the evaluation error itself.
+# kernel_tie_tolerance() is the error of the HIP kernel's E, derived from its arithmetic, entry by entry.
+LOG2E = 1.4426950408889634
+LN2 = 0.6931471805599453
+ACC_BIAS = 1.5 * 2.0**23  # start value of the kernel's integer accumulators, read as a float
+
+
+def kernel_tie_tolerance(x_nat, m_new_nat, c_log2, folded):
+    """Relative error bound of the kernel's E = qmaxP * 2^(c*S - m' - e) for one tile.
+    x_nat [rows, cols], m_new_nat [rows]: logits and running maxima in natural-log units (as the
+    oracle holds them); c_log2: the tile's logit scale in log2 units per integer step.
+
+    The exponent is ONE fp32 fma of exact integers plus an offset: its rounding is half an ulp of
+    the result, |y| * 2^-24 with |y| <= |x - m'| + 8 (log2 of qmaxP and e <= 0 shift the tile by a
+    few octaves); the offset itself (m', e and constants, |m'| + 40 at most) comes from a handful of
+    fp32 operations, 4 half-ulps; v_exp_f32 is good to about 1 ulp, 2^-23.  With the accumulator
+    bias folded into the offset (8-bit P codes) the offset has the magnitude c * 1.5 * 2^23 and is
+    rounded once more, half an ulp of that; its exact residue is applied to the block's weight, so
+    it perturbs the codes only.  Errors of an exponent turn into relative errors of E times ln 2."""
+    x2 = np.abs(x_nat - m_new_nat[:, None]) * LOG2E
+    m2 = np.abs(m_new_nat)[:, None] * LOG2E
+    err_exponent = 2.0**-24 * (x2 + 8.0) + 4 * 2.0**-24 * (m2 + 40.0)
+    if folded:
+        err_exponent = err_exponent + 2.0**-23 * (c_log2 * ACC_BIAS + m2 + 40.0)
+    return LN2 * err_exponent + 2.0**-23
 
 
 class TieRisk:
     """Observer of ``po.sparse_attention_head``: per output element, the first-order bound on what
-    flipping every P code within ``tol`` (relative) of a rounding tie can change.  Every near-tie
-    entry contributes sP * sv * |Vc| of its key; the contributions are carried through the same
-    rescaling recurrence as the accumulator and divided by the same denominator."""
+    flipping every P code within the kernel's evaluation error of a rounding tie can change.  Every
+    near-tie entry contributes sP * sv * |Vc| of its key; the contributions are carried through the
+    same rescaling recurrence as the accumulator and divided by the same denominator.
+    ``tol`` fixes one relative tolerance for all entries (used by the hand-worked test); otherwise
+    the tolerance is kernel_tie_tolerance() of each tile (``sq``, ``sk``, ``d`` give its logit scale;
+    ``folded`` [k] says for which row blocks the kernel folds the accumulator bias into the exponent)."""
 
-    def __init__(self, vc, sv, block, n_valid, tol):
+    def __init__(self, vc, sv, block, n_valid, tol=None, sq=None, sk=None, d=None, folded=None, code_gain=1.0):
         self.absv = np.abs(np.asarray(vc, np.float64))
         self.sv = np.asarray(sv, np.float64)
         self.block, self.n_valid, self.tol = block, n_valid, tol
+        self.sq, self.sk, self.d, self.folded = sq, sk, d, folded
+        self.code_gain = code_gain  # factor by which the kernel's integer products exceed the plain code products
         self.out = np.zeros(self.absv.shape, np.float64)
         self._risk = None
         self._row = None
 
-    def visit(self, i, j, p, codes, s_p, alpha):
+    def visit(self, i, j, x, m_new, p, codes, s_p, alpha):
         if self._row != i:
             self._row, self._risk = i, np.zeros((p.shape[0], self.absv.shape[1]))
         self._risk = alpha[:, None] * self._risk
@@ -49,7 +72,12 @@ class TieRisk:
             return
         c0 = j * self.block
         e = p / s_p
-        near = np.abs(np.abs(e - np.rint(e)) - 0.5) <= self.tol * e + 1e-12
+        if self.tol is not None:
+            tol = self.tol
+        else:
+            c_log2 = float(self.sq[i]) * float(self.sk[j]) * LOG2E / np.sqrt(self.d) / self.code_gain
+            tol = kernel_tie_tolerance(x, m_new, c_log2, self.folded is not None and bool(self.folded[i]))
+        near = np.abs(np.abs(e - np.rint(e)) - 0.5) <= tol * e + 1e-12
         self._risk += (near.astype(np.float64) @ self.absv[c0 : c0 + p.shape[1]]) * (s_p * self.sv[j])
 
     def row_block_done(self, i, l):
@@ -61,6 +89,23 @@ class TieRisk:
         self._row = None
 
 
+def tie_risk_for(vc, sv, sq, sk, block, n_valid, d, bits_qk, bits_pv, row_ptr_h, col_idx):
+    """The kernel folds the accumulator bias into the exponent only where P has 8-bit codes (with 4-bit
+    codes one flipped code moves an element by up to a seventh of its largest term) and only for row
+    blocks whose largest tile scale keeps the offset below 2^13; 4-bit Q and K codes enter its integer
+    product times 16 each, so one integer step is 1/256 of a plain code step."""
+    k = len(sq)
+    gain = 256.0 if bits_qk == 4 else 1.0
+    folded = np.zeros(k, bool)
+    if bits_pv == 8:
+        for i in range(k):
+            cols = col_idx[int(row_ptr_h[i]) : int(row_ptr_h[i + 1])]
+            if len(cols):
+                c_max = float(sq[i]) * float(np.max(np.asarray(sk)[cols])) * LOG2E / np.sqrt(d) / gain
+                folded[i] = c_max * ACC_BIAS < 8192.0
+    return TieRisk(vc, sv, block, n_valid, sq=sq, sk=sk, d=d, folded=folded, code_gain=gain)
+
+
 def oracle_head(w, q, k, v, perm_id, row_ptr_h, col_idx, row_blocks=None):
     """All intermediate results of the oracle for one head.  q, k, v: [N, d] float32."""
     idx = po.perm_index(w.F, w.Hg, w.Wg, w.T_text, int(perm_id))
@@ -70,7 +115,7 @@ def oracle_head(w, q, k, v, perm_id, row_ptr_h, col_idx, row_blocks=None):
     vc, sv = po.prepare_operand(v, idx, w.npad, w.block, w.bits_pv)
     out.update(qc=qc, sq=sq, kc=kc, sk=sk, vc=vc, sv=sv)
     qmax_p = None if w.bits_pv in (0, 16) else po.qmax_of(w.bits_pv)
-    risk = TieRisk(vc, sv, w.block, w.N, KERNEL_TIE_TOL)
+    risk = tie_risk_for(vc, sv, sq, sk, w.block, w.N, w.d, w.bits_qk, w.bits_pv, row_ptr_h, col_idx)
     op = po.sparse_attention_head(qc, sq, kc, sk, vc, sv, w.N, w.block, row_ptr_h, col_idx, qmax_p, row_blocks, observer=risk)
     out["op"] = op
     out["flip_risk"] = risk.out
@@ -118,14 +163,14 @@ def check_attention(got, ref, risk, max_abs, rel, what=""):
 # numpy and the oracle), so they are safe to start from a process that has already initialised the GPU.
 # ---------------------------------------------------------------------------------------------
 def _oracle_rows_job(job):
-    (dims, q, k, v, perm_id, row_ptr_h, col_idx, row_blocks, tol) = job
+    (dims, q, k, v, perm_id, row_ptr_h, col_idx, row_blocks) = job
     F, Hg, Wg, T_text, n, npad, block, bits_qk, bits_pv = dims
     idx = po.perm_index(F, Hg, Wg, T_text, int(perm_id))
     qc, sq = po.prepare_operand(q, idx, npad, block, bits_qk)
     kc, sk = po.prepare_operand(k, idx, npad, block, bits_qk)
     vc, sv = po.prepare_operand(v, idx, npad, block, bits_pv)
     qmax_p = None if bits_pv in (0, 16) else po.qmax_of(bits_pv)
-    risk = TieRisk(vc, sv, block, n, tol)
+    risk = tie_risk_for(vc, sv, sq, sk, block, n, q.shape[1], bits_qk, bits_pv, row_ptr_h, col_idx)
     op = po.sparse_attention_head(qc, sq, kc, sk, vc, sv, n, block, row_ptr_h, col_idx, qmax_p, row_blocks, observer=risk)
     rows = np.concatenate([np.arange(i * block, min((i + 1) * block, n)) for i in row_blocks])
     return rows, op[rows], risk.out[rows]
@@ -151,7 +196,7 @@ def oracle_whole_heads(w, heads, qkv_of_head, perm_ids, row_ptr, col_idx, worker
         chunks = [sorted(int(i) for i in order[c::per]) for c in range(per)]
         for rows in chunks:
             if rows:
-                jobs.append((dims, q, k, v, int(perm_ids[h]), row_ptr[h], col_idx, rows, KERNEL_TIE_TOL))
+                jobs.append((dims, q, k, v, int(perm_ids[h]), row_ptr[h], col_idx, rows))
                 owner.append(h)
     out = {h: (np.zeros((w.npad, w.d)), np.zeros((w.npad, w.d))) for h in heads}
     with ProcessPoolExecutor(max_workers=workers, mp_context=mp.get_context("spawn")) as ex:

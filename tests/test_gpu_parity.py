@@ -342,7 +342,11 @@ def test_row_maximum_climbing_hundreds_of_octaves(bits):
         assert np.isfinite(o[0, h]).all()
         st = check_attention(o[0, h], r["o"], po.unpermute(r["flip_risk"], r["idx"]), MAX_ABS, REL_L2_BF16 if bits == 16 else REL_L2,
                              "steep head %d" % h)
-        assert st["rel_l2"] < 1e-3
+        # With fp32 output the error left is that of the arithmetic.  With 8-bit P codes the kernel forms the
+        # exponent as c*(B + S) + offset: the offset's rounding grows with the logit scale c (here the logits
+        # span hundreds of octaves, several times a real layer's), flips more near-tie codes, and is the
+        # larger part of what is left; the other modes keep the exact exponent.
+        assert st["rel_l2"] < (3e-3 if bits == 8 else 1e-3)
 
 
 @pytest.mark.parametrize("scale", [1e-3, 1e-6, 30.0])

@@ -9,6 +9,7 @@ import pytest
 
 from oracle import paro_oracle as po
 from paper_2506_16054_amd import binding as pb
+from paper_2506_16054_amd import workloads as wl
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -239,3 +240,42 @@ def test_row_schedule_is_a_permutation_heaviest_first_within_l2_groups():
                 assert np.all(np.diff(lv[groups == gidx]) <= 0)
     with pytest.raises(pb.ParoError):
         pb.paro_schedule_rows(s2, 5, 8, rp2)
+
+
+def test_blocklist_and_launch_order_validators():
+    """Lists the library makes pass; each way a caller-made list can break the kernels' assumptions is named."""
+    w = wl.Workload("chk", 1, 2, 64, 2, 6, 8, 0, 32, 0.5, 8, 8, "f32", 5, perm_choice=(0, 3))
+    s = pb.shape_of(w)
+    masks = wl.make_block_masks(w, lambda pid: pb.paro_perm_index(s, pid), wl.make_perm_ids(w))
+    row_ptr, col_idx = pb.paro_mask_to_blocklist(w.nh, w.k, wl.pack_bitmask(masks))
+    pb.paro_check_blocklist(w.nh, w.k, row_ptr, col_idx)
+    order = pb.paro_schedule_rows(s, 8, 8, row_ptr)
+    pb.paro_check_row_order(s, order)
+
+    def rejected(fn, *a):
+        with pytest.raises(pb.ParoError) as e:
+            fn(*a)
+        assert e.value.status == pb.PARO_EINVAL
+        return str(e.value)
+
+    row = next(i for i in range(w.k) if row_ptr[0, i + 1] - row_ptr[0, i] >= 2)
+    beg = int(row_ptr[0, row])
+    swapped = col_idx.copy()
+    swapped[beg], swapped[beg + 1] = col_idx[beg + 1], col_idx[beg]
+    assert "not strictly ascending" in rejected(pb.paro_check_blocklist, w.nh, w.k, row_ptr, swapped)
+    dup = col_idx.copy()
+    dup[beg + 1] = dup[beg]
+    assert "not strictly ascending" in rejected(pb.paro_check_blocklist, w.nh, w.k, row_ptr, dup)
+    far = col_idx.copy()
+    far[beg] = w.k
+    assert "outside" in rejected(pb.paro_check_blocklist, w.nh, w.k, row_ptr, far)
+    bad_ptr = row_ptr.copy()
+    bad_ptr[1, 2] = bad_ptr[1, 3] + 1
+    assert "ascending range" in rejected(pb.paro_check_blocklist, w.nh, w.k, bad_ptr, col_idx)
+    assert "ascending range" in rejected(pb.paro_check_blocklist, w.nh, w.k, row_ptr, col_idx[:-1])
+    twice = order.copy()
+    twice[3] = twice[4]
+    assert "appears twice" in rejected(pb.paro_check_row_order, s, twice)
+    out = order.copy()
+    out[0] = order.size
+    assert "outside" in rejected(pb.paro_check_row_order, s, out)

@@ -360,7 +360,7 @@ def test_tie_risk_bounds_the_effect_of_a_rounding_tie():
     v = np.array([[3.0], [-5.0]])
     ones = np.ones(1, np.float32)
     rp, ci = np.array([0, 1], np.int32), np.array([0], np.int32)
-    risk = TieRisk(v, ones, block, n, 1e-9)
+    risk = TieRisk(v, ones, block, n, tol=1e-9)
     o = po.sparse_attention_head(q, ones, k, ones, v, ones, n, block, rp, ci, 127, observer=risk)
     assert np.array_equal(o, po.sparse_attention_head(q, ones, k, ones, v, ones, n, block, rp, ci, 127))  # observing changes nothing
     l = 1.5
@@ -370,7 +370,7 @@ def test_tie_risk_bounds_the_effect_of_a_rounding_tie():
     assert np.allclose(risk.out[:, 0], 5.0 / 127 / l, rtol=1e-12)
     assert abs(up - down) <= risk.out[0, 0] * (1 + 1e-12)
     # away from ties nothing is flagged
-    risk2 = TieRisk(v, ones, block, n, 1e-9)
+    risk2 = TieRisk(v, ones, block, n, tol=1e-9)
     k2 = np.array([[0.0], [-0.3]])
     po.sparse_attention_head(q, ones, k2, ones, v, ones, n, block, rp, ci, 127, observer=risk2)
     assert np.all(risk2.out == 0)
