@@ -575,6 +575,288 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 }
 
 // -------------------------------------------------------------------------------------------
+// d = 64, block 64, 8-bit Q and K codes, 8-bit P and V codes: ONE wavefront per row block, no barrier.
+//
+// The wavefront owns all 64 queries of the row block as two halves of 32 (H = 0, 1; a lane holds query
+// n of each half).  The P quantization group - the whole 64 x 64 tile - then lives in one wavefront: its
+// maximum is an in-wave reduction, nothing is exchanged between wavefronts and nothing has to be
+// synchronised.  K_j and V_j^T travel from global memory (L2) straight into LDS with
+// global_load_lds_dwordx4, which bypasses the vector registers: every lane fetches exactly the 16-byte
+// fragments the matrix instructions will take from it as A operand (K rows and PARO_VT rows are 64 bytes;
+// a lane pair reads 32 contiguous bytes), so a tile arrives in LDS as eight 1 KB fragments in lane order
+// and is read back with conflict-free 16-byte LDS reads just before use.  The LDS is a private two-slot
+// ring per wavefront: block t+1 is requested at the top of block t and has all of block t to arrive; the
+// only wait is one vmcnt(0) per block.  Each fragment feeds two matrix instructions (one per half).
+// Per block and half the arithmetic is that of attn_i8_kernel.
+// -------------------------------------------------------------------------------------------
+#ifndef PARO_ATTN_SINGLE_WAVE
+#define PARO_ATTN_SINGLE_WAVE 1
+#endif
+
+__device__ inline void lds_dma16(const uint8_t* src, uint8_t* lds_dst) {
+    // lane L's 16 bytes at src (per lane) land at lds_dst (wave-uniform) + 16 L
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src, (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
+}
+
+template <typename OutT>
+__global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
+    constexpr int BLK = 64, D = 64;
+    constexpr float LOG2_QMAXP = 6.988684686772166f;
+    constexpr float kLog2_65535 = 15.999977986052736f;
+    __shared__ __attribute__((aligned(16))) uint8_t ring[2][8][1024];  // [slot][fragment: 0-3 K (T,s), 4-7 V (dt,T)][16 B per lane]
+
+    const int wg = blockIdx.x;
+    const int logical = (wg & 7) * a.per_xcd + (wg >> 3);
+    if (logical >= a.total_wg) return;
+    const int item = a.row_order ? min(max(a.row_order[logical], 0), a.total_wg - 1) : logical;
+    const int bh = item / a.kblocks;
+    const int i = item - bh * a.kblocks;
+    const int h = bh % a.nh;
+    const int lane = threadIdx.x;
+    const int n = lane & 31;
+    const int g = lane >> 5;
+
+    const int* rp = a.row_ptr + (size_t)h * (a.kblocks + 1) + i;
+    const int beg = __builtin_amdgcn_readfirstlane(min(max(rp[0], 0), a.nnz));
+    const int end = __builtin_amdgcn_readfirstlane(min(max(rp[1], beg), a.nnz));
+    const int cnt = end - beg;
+    const int* cols = a.col_idx + beg;
+    if (2 * cnt > a.kblocks) __builtin_amdgcn_s_setprio(2);
+
+    const size_t head_rows = (size_t)bh * a.kblocks * BLK;
+    const uint8_t* kbase = a.k + head_rows * D + n * D + 16 * g;    // this lane's K fragment of key tile 0, step 0
+    const uint8_t* vbase = a.v + head_rows * D + n * BLK + 16 * g;  // this lane's V^T fragment of channel tile 0, key tile 0
+    const float* skp = a.sk + (size_t)bh * a.kblocks;
+    const float* svp = a.sv + (size_t)bh * a.kblocks;
+    const float sq_i = a.sq[(size_t)bh * a.kblocks + i] * a.qk_scale;
+    int row[2];
+    bool row_valid[2];
+    v4i qf[2][2];  // [half][contraction step]
+#pragma unroll
+    for (int H = 0; H < 2; ++H) {
+        row[H] = i * BLK + 32 * H + n;
+        row_valid[H] = row[H] < a.n_tokens;
+        const uint8_t* qrow = a.q + (head_rows + row[H]) * D + 16 * g;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) qf[H][s] = *(const v4i*)(qrow + 32 * s);
+    }
+
+    // column indices: 64 per fetch, one per lane, one chunk ahead
+    auto load_cols = [&](int chunk) {
+        const int idx = min(chunk * 64 + lane, cnt - 1);
+        return cnt > 0 && chunk * 64 < cnt ? min(max(cols[idx], 0), a.kblocks - 1) : 0;
+    };
+    int cols_cur = load_cols(0), cols_nxt = load_cols(1);
+    int cur_chunk = 0;  // chunk held by cols_cur
+
+    // request the tiles of column block j into ring slot `slot`
+    auto request = [&](int j, int slot) {
+        const uint8_t* kp = kbase + (size_t)j * (BLK * D);
+        const uint8_t* vp = vbase + (size_t)j * (BLK * D);
+#pragma unroll
+        for (int T = 0; T < 2; ++T)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) lds_dma16(kp + T * (32 * D) + 32 * s, &ring[slot][2 * T + s][0]);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int T = 0; T < 2; ++T) lds_dma16(vp + dt * (32 * BLK) + 32 * T, &ring[slot][4 + 2 * dt + T][0]);
+    };
+
+    float m[2] = {-INFINITY, -INFINITY};
+    float m_ref[2] = {-INFINITY, -INFINITY};
+    float w_base[2] = {INFINITY, INFINITY};
+    float l[2] = {0.0f, 0.0f};
+    float acc[2][2][16];  // [half][channel tile][register]
+#pragma unroll
+    for (int H = 0; H < 2; ++H)
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[H][dt][r] = 0.0f;
+    v16i acc_init;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc_init[r] = kAccBiasI;
+    asm volatile("" : "+v"(acc_init));
+
+    float sk_cur = 0.0f, sv_cur = 0.0f;
+    int j_cur = 0;
+    if (cnt > 0) {
+        j_cur = __builtin_amdgcn_readlane(cols_cur, 0);
+        request(j_cur, 0);
+        sk_cur = skp[j_cur];
+        sv_cur = svp[j_cur];
+    }
+    const int tail_block = (a.n_tokens % BLK) != 0 ? a.kblocks - 1 : -1;  // the column block with padded keys, if any
+
+    auto step = [&](auto fold_tag, int t) {
+        constexpr bool FOLD = decltype(fold_tag)::value;
+        const float c = sq_i * sk_cur;
+        const float sv_now = sv_cur;
+        const int j_now = j_cur;
+        const uint8_t* slot = &ring[t & 1][0][0] + 16 * lane;
+
+        // ---- the tiles of this block have arrived (everything this wavefront has in flight is theirs)
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0); the other counters untouched
+        v4i kf[2][2];
+#pragma unroll
+        for (int T = 0; T < 2; ++T)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) kf[T][s] = *(const v4i*)(slot + (2 * T + s) * 1024);
+        // ---- request the next block's tiles into the other slot (its previous content, block t-1, is consumed)
+        if (t + 1 < cnt) {
+            if (((t + 1) & 63) == 0) {
+                cols_cur = cols_nxt;
+                ++cur_chunk;
+                cols_nxt = load_cols(cur_chunk + 1);
+            }
+            j_cur = __builtin_amdgcn_readlane(cols_cur, (t + 1) & 63);
+            request(j_cur, (t + 1) & 1);
+            sk_cur = skp[j_cur];
+            sv_cur = svp[j_cur];
+        }
+
+        // ---- S^T = K_j Q_i^T for both halves (i32, biased); every K fragment feeds two products
+        v16i sacc[2][2];  // [half][key tile]
+#pragma unroll
+        for (int T = 0; T < 2; ++T)
+#pragma unroll
+            for (int H = 0; H < 2; ++H) {
+                sacc[H][T] = acc_init;
+#pragma unroll
+                for (int s = 0; s < 2; ++s) sacc[H][T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[T][s], qf[H][s], sacc[H][T], 0, 0, 0);
+            }
+        // Keys past N (ragged last column block) never receive probability mass: their raw logits become the
+        // bit pattern of -inf, which as an integer loses every maximum and as a float sends the exponent's fma
+        // (c > 0) to -inf, i.e. E = 0.  A wave-uniform branch, taken for that one column block only.
+        if (j_now == tail_block) {
+            const int nkeys = a.n_tokens - (a.kblocks - 1) * BLK;
+#pragma unroll
+            for (int H = 0; H < 2; ++H)
+#pragma unroll
+                for (int T = 0; T < 2; ++T)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (32 * T + 8 * (r >> 2) + 4 * g + (r & 3) >= nkeys) sacc[H][T][r] = (int)0xFF800000;
+        }
+
+        // ---- running maxima of both halves and the tile's quantization scale (one in-wave reduction)
+        float m_new[2];
+        unsigned eb = 0xFF800000u;
+#pragma unroll
+        for (int H = 0; H < 2; ++H) {
+            int part[4] = {0, 0, 0, 0};  // below every real value (those carry the accumulator bias)
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) part[r & 3] = max(part[r & 3], sacc[H][T][r]);
+            const float ymax = c * int_result(xor32_max(max(max(part[0], part[1]), max(part[2], part[3]))));
+            m_new[H] = fmaxf(m[H], ymax);
+            if (row_valid[H]) eb = min(eb, __float_as_uint(ymax - m_new[H]));
+        }
+        const float e = __uint_as_float(wave_umin(eb));
+        if (__builtin_amdgcn_ballot_w64(m_new[0] - m_ref[0] > 64.0f || m_new[1] - m_ref[1] > 64.0f) != 0) {
+#pragma unroll
+            for (int H = 0; H < 2; ++H) {
+                const float down = __builtin_amdgcn_exp2f(m_ref[H] - m_new[H]);  // first block: 2^-inf = 0 on zero sums
+                l[H] *= down;
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[H][dt][r] *= down;
+                m_ref[H] = m_new[H];
+                w_base[H] = -kLog2_65535 - m_new[H];
+            }
+        }
+        v4i vf[2][2];  // V_j^T fragments [channel tile][key tile]
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int T = 0; T < 2; ++T) vf[dt][T] = *(const v4i*)(slot + (4 + 2 * dt + T) * 1024);
+
+        float cb_hi = 0.0f, cb_lo = 0.0f;
+        if constexpr (FOLD) {
+            cb_hi = c * kAccBiasF;
+            cb_lo = fmaf(c, kAccBiasF, -cb_hi);
+        }
+#pragma unroll
+        for (int H = 0; H < 2; ++H) {
+            m[H] = m_new[H];
+            const float off_n = (LOG2_QMAXP - kLog2_65535) - m_new[H] - e;
+            float off_f = off_n, w_blk;
+            if constexpr (FOLD) {
+                off_f = off_n - cb_hi;
+                const float bb = off_f - off_n;
+                const float terr = (off_n - (off_f - bb)) + (-cb_hi - bb);
+                w_blk = __builtin_amdgcn_exp2f((w_base[H] - off_n) - (cb_lo - terr));
+            } else {
+                w_blk = __builtin_amdgcn_exp2f(w_base[H] - off_n);
+            }
+            // ---- E, row sum, codes packed as B operand
+            float rs = 0.0f;
+            v4i pf[2];
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    float ev[4];
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) {
+                        ev[p] = __builtin_amdgcn_exp2f(fmaf(FOLD ? __int_as_float(sacc[H][T][4 * qd + p]) : int_result(sacc[H][T][4 * qd + p]), c, off_f));
+                        rs = (T == 0 && qd == 0 && p == 0) ? ev[p] : rs + ev[p];
+                    }
+                    const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[0], ev[1]));
+                    const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[2], ev[3]));
+                    pf[T][qd] = (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u);
+                }
+            l[H] = fmaf(rs, w_blk, l[H]);
+            // ---- O^T += (sP sv_j 2^(m' - m_ref)) V_j^T P^T for this half
+            const float sv_eff = w_blk * sv_now;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt) {
+                v16i o = acc_init;
+#pragma unroll
+                for (int T = 0; T < 2; ++T) o = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[dt][T], pf[T], o, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[H][dt][r] = fmaf(int_result(o[r]), sv_eff, acc[H][dt][r]);
+            }
+        }
+    };
+
+    constexpr bool FOLDABLE = PARO_FOLD_LOGIT_BIAS;
+    bool fold = false;
+    if constexpr (FOLDABLE) {  // same rule as attn_i8_kernel
+        float sk_max = 0.0f;
+        for (int base = 0; base < cnt; base += 64)
+            if (base + lane < cnt) sk_max = fmaxf(sk_max, skp[min(max(cols[base + lane], 0), a.kblocks - 1)]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) sk_max = fmaxf(sk_max, __shfl_xor(sk_max, off));
+        fold = sq_i * sk_max * kAccBiasF < 8192.0f;
+    }
+    if (fold) {
+        for (int t = 0; t < cnt; ++t) step(std::bool_constant<FOLDABLE>{}, t);
+    } else {
+        for (int t = 0; t < cnt; ++t) step(std::false_type{}, t);
+    }
+
+#pragma unroll
+    for (int H = 0; H < 2; ++H) {
+        const float l_tot = (l[H] + __shfl_xor(l[H], 32)) * 65535.0f;
+        const float inv = (row_valid[H] && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
+        const long long ooff = out_row_offset<D>(a, bh, h, head_rows, row[H], row_valid[H]);
+        if (ooff >= 0) {
+            OutT* orow = (OutT*)a.op + ooff + 4 * g;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd)
+                    store4(orow + 32 * dt + 8 * qd, acc[H][dt][4 * qd] * inv, acc[H][dt][4 * qd + 1] * inv, acc[H][dt][4 * qd + 2] * inv,
+                           acc[H][dt][4 * qd + 3] * inv);
+        }
+    }
+}
+
+// -------------------------------------------------------------------------------------------
 // bf16 unquantized block-sparse mode (the sparse-only rows of the paper's tables): same work
 // split, transposed orientation and block list, on v_mfma_f32_32x32x16_bf16.  P is not quantized,
 // so there is no tile-wide scale and no cross-wavefront exchange; P enters the PV product rounded
@@ -857,6 +1139,14 @@ static void launch_rawq_shape(int d, int bits_pv, paro_dtype out_dtype, const At
 
 template <int QKBITS, int PVBITS>
 static void launch_i8(int blk, int d, paro_dtype out_dtype, const AttnArgs& a, hipStream_t st) {
+    if constexpr (PARO_ATTN_SINGLE_WAVE && QKBITS == 8 && PVBITS == 8) {
+        if (blk == 64 && d == 64) {  // one wavefront per row block
+            dim3 grid((unsigned)(a.per_xcd * 8));
+            if (out_dtype == PARO_F32) hipLaunchKernelGGL((attn_i8_w64_kernel<float>), grid, dim3(64), 0, st, a);
+            else hipLaunchKernelGGL((attn_i8_w64_kernel<uint16_t>), grid, dim3(64), 0, st, a);
+            return;
+        }
+    }
     if (blk == 64 && d == 64) launch_out<64, 64, QKBITS, PVBITS>(out_dtype, a, st);
     else if (blk == 64 && d == 128) launch_out<64, 128, QKBITS, PVBITS>(out_dtype, a, st);
     else if (blk == 32 && d == 64) launch_out<32, 64, QKBITS, PVBITS>(out_dtype, a, st);
