@@ -236,7 +236,10 @@ __global__ __launch_bounds__(1024) void block_kernel(int iters, WaveTimes* __res
     const int wave = threadIdx.x >> 6;
     const int waves = blockDim.x >> 6;
     const int lane = threadIdx.x & 63;
-    v4i kf = {lane, 2, 3, 4}, qf = {5, 6, 7, lane}, vf = {lane, 9, 1, 2};
+    // distinct, compiler-opaque operands per key tile / channel tile, so that no product or exponential of one
+    // tile can be reused for the other
+    v4i kf[2] = {{lane, 2, 3, 4}, {lane + 1, 5, 3, 4}}, qf = {5, 6, 7, lane}, vf[2] = {{lane, 9, 1, 2}, {lane + 3, 9, 7, 2}};
+    asm volatile("" : "+v"(kf[0]), "+v"(kf[1]), "+v"(vf[0]), "+v"(vf[1]), "+v"(qf));
     v16i init;
 #pragma unroll
     for (int r = 0; r < 16; ++r) init[r] = 0x4B400000;
@@ -256,10 +259,11 @@ __global__ __launch_bounds__(1024) void block_kernel(int iters, WaveTimes* __res
         for (int T = 0; T < 2; ++T) {
             s[T] = init;
             if constexpr (PARTS & 1) {
-                s[T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf, s[T], 0, 0, 0);
-                s[T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf, s[T], 0, 0, 0);
+                s[T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[T], qf, s[T], 0, 0, 0);
+                s[T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[1 - T], qf, s[T], 0, 0, 0);
             } else {
-                s[T][0] += kf[0] + it;
+                s[T][0] += kf[T][0] + it;
+                s[T][7] += kf[T][1] - it;
             }
         }
         int part[4] = {0, 0, 0, 0};
@@ -303,8 +307,8 @@ __global__ __launch_bounds__(1024) void block_kernel(int iters, WaveTimes* __res
         for (int d = 0; d < 2; ++d) {
             v16i o = init;
             if constexpr (PARTS & 1) {
-                o = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf[0], o, 0, 0, 0);
-                o = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf[1], o, 0, 0, 0);
+                o = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[d], pf[0], o, 0, 0, 0);
+                o = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[1 - d], pf[1], o, 0, 0, 0);
             } else {
                 o[0] += pf[0][d] ^ pf[1][d + 2];
                 o[5] += pf[0][d + 2] ^ pf[1][d];
@@ -312,7 +316,8 @@ __global__ __launch_bounds__(1024) void block_kernel(int iters, WaveTimes* __res
 #pragma unroll
             for (int r = 0; r < ((PARTS & 16) ? 16 : 1); ++r) acc[d][r] = fmaf(__int_as_float(o[r]) - 12582912.0f, w, acc[d][r]);
         }
-        kf[1] ^= it;
+        kf[0][1] ^= it;
+        kf[1][2] += it;
     }
     const long long c1 = __builtin_readcyclecounter();
     const long long t1 = wall_clock64();

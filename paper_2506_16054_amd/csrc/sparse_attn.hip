@@ -575,7 +575,7 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 }
 
 // -------------------------------------------------------------------------------------------
-// d = 64, block 64, 8-bit Q and K codes, 8-bit P and V codes: ONE wavefront per row block, no barrier.
+// d = 64, block 64, 8-bit Q and K codes (P and V 8-bit or 4-bit): ONE wavefront per row block, no barrier.
 //
 // The wavefront owns all 64 queries of the row block as two halves of 32 (H = 0, 1; a lane holds query
 // n of each half).  The P quantization group - the whole 64 x 64 tile - then lives in one wavefront: its
@@ -598,12 +598,15 @@ __device__ inline void lds_dma16(const uint8_t* src, uint8_t* lds_dst) {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src, (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
 }
 
-template <typename OutT>
+template <int PVBITS, typename OutT>
 __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
     constexpr int BLK = 64, D = 64;
-    constexpr float LOG2_QMAXP = 6.988684686772166f;
+    constexpr int VPACK = PVBITS == 4 ? 2 : 1;
+    constexpr float LOG2_QMAXP = PVBITS == 4 ? 2.807354922057604f : 6.988684686772166f;
     constexpr float kLog2_65535 = 15.999977986052736f;
-    __shared__ __attribute__((aligned(16))) uint8_t ring[2][8][1024];  // [slot][fragment: 0-3 K (T,s), 4-7 V (dt,T)][16 B per lane]
+    // [slot][fragment][16 B per lane]; fragments 0-3: K (T,s); 4-7: V^T (dt,T) - with 4-bit V only 4-5: (dt), where
+    // lane (n, g) holds bytes 16g .. 16g+15 of packed channel row 32 dt + n, i.e. the 32 slots of key tile g
+    __shared__ __attribute__((aligned(16))) uint8_t ring[2][8][1024];
 
     const int wg = blockIdx.x;
     const int logical = (wg & 7) * a.per_xcd + (wg >> 3);
@@ -625,7 +628,7 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
 
     const size_t head_rows = (size_t)bh * a.kblocks * BLK;
     const uint8_t* kbase = a.k + head_rows * D + n * D + 16 * g;    // this lane's K fragment of key tile 0, step 0
-    const uint8_t* vbase = a.v + head_rows * D + n * BLK + 16 * g;  // this lane's V^T fragment of channel tile 0, key tile 0
+    const uint8_t* vbase = a.v + head_rows * D / VPACK + n * (BLK / VPACK) + 16 * g;  // this lane's V^T piece of channel tile 0
     const float* skp = a.sk + (size_t)bh * a.kblocks;
     const float* svp = a.sv + (size_t)bh * a.kblocks;
     const float sq_i = a.sq[(size_t)bh * a.kblocks + i] * a.qk_scale;
@@ -652,15 +655,20 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
     // request the tiles of column block j into ring slot `slot`
     auto request = [&](int j, int slot) {
         const uint8_t* kp = kbase + (size_t)j * (BLK * D);
-        const uint8_t* vp = vbase + (size_t)j * (BLK * D);
+        const uint8_t* vp = vbase + (size_t)j * (BLK * D / VPACK);
 #pragma unroll
         for (int T = 0; T < 2; ++T)
 #pragma unroll
             for (int s = 0; s < 2; ++s) lds_dma16(kp + T * (32 * D) + 32 * s, &ring[slot][2 * T + s][0]);
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
+        for (int dt = 0; dt < 2; ++dt) {
+            if constexpr (PVBITS == 4) {
+                lds_dma16(vp + dt * (32 * BLK / 2), &ring[slot][4 + dt][0]);
+            } else {
 #pragma unroll
-            for (int T = 0; T < 2; ++T) lds_dma16(vp + dt * (32 * BLK) + 32 * T, &ring[slot][4 + 2 * dt + T][0]);
+                for (int T = 0; T < 2; ++T) lds_dma16(vp + dt * (32 * BLK) + 32 * T, &ring[slot][4 + 2 * dt + T][0]);
+            }
+        }
     };
 
     float m[2] = {-INFINITY, -INFINITY};
@@ -772,7 +780,18 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-            for (int T = 0; T < 2; ++T) vf[dt][T] = *(const v4i*)(slot + (4 + 2 * dt + T) * 1024);
+            for (int T = 0; T < 2; ++T) {
+                if constexpr (PVBITS == 4) {
+                    // this lane's 16 slots of key tile T: 8 packed bytes inside the piece that lane (n, T) fetched;
+                    // a nibble moved to the top of its byte is the code times 16 (undone in the scale), and the
+                    // PARO_VT nibble order makes the bytes come out in slot order
+                    const uint2 x = *(const uint2*)(&ring[t & 1][4 + dt][0] + (n + 32 * T) * 16 + 8 * g);
+                    vf[dt][T] = v4i{(int)((x.x << 4) & 0xF0F0F0F0u), (int)(x.x & 0xF0F0F0F0u), (int)((x.y << 4) & 0xF0F0F0F0u),
+                                    (int)(x.y & 0xF0F0F0F0u)};
+                } else {
+                    vf[dt][T] = *(const v4i*)(slot + (4 + 2 * dt + T) * 1024);
+                }
+            }
 
         float cb_hi = 0.0f, cb_lo = 0.0f;
         if constexpr (FOLD) {
@@ -811,7 +830,7 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
                 }
             l[H] = fmaf(rs, w_blk, l[H]);
             // ---- O^T += (sP sv_j 2^(m' - m_ref)) V_j^T P^T for this half
-            const float sv_eff = w_blk * sv_now;
+            const float sv_eff = w_blk * sv_now * (PVBITS == 4 ? 0.0625f : 1.0f);
 #pragma unroll
             for (int dt = 0; dt < 2; ++dt) {
                 v16i o = acc_init;
@@ -823,7 +842,7 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
         }
     };
 
-    constexpr bool FOLDABLE = PARO_FOLD_LOGIT_BIAS;
+    constexpr bool FOLDABLE = PARO_FOLD_LOGIT_BIAS && PVBITS == 8;
     bool fold = false;
     if constexpr (FOLDABLE) {  // same rule as attn_i8_kernel
         float sk_max = 0.0f;
@@ -1139,11 +1158,11 @@ static void launch_rawq_shape(int d, int bits_pv, paro_dtype out_dtype, const At
 
 template <int QKBITS, int PVBITS>
 static void launch_i8(int blk, int d, paro_dtype out_dtype, const AttnArgs& a, hipStream_t st) {
-    if constexpr (PARO_ATTN_SINGLE_WAVE && QKBITS == 8 && PVBITS == 8) {
+    if constexpr (PARO_ATTN_SINGLE_WAVE && QKBITS == 8) {
         if (blk == 64 && d == 64) {  // one wavefront per row block
             dim3 grid((unsigned)(a.per_xcd * 8));
-            if (out_dtype == PARO_F32) hipLaunchKernelGGL((attn_i8_w64_kernel<float>), grid, dim3(64), 0, st, a);
-            else hipLaunchKernelGGL((attn_i8_w64_kernel<uint16_t>), grid, dim3(64), 0, st, a);
+            if (out_dtype == PARO_F32) hipLaunchKernelGGL((attn_i8_w64_kernel<PVBITS, float>), grid, dim3(64), 0, st, a);
+            else hipLaunchKernelGGL((attn_i8_w64_kernel<PVBITS, uint16_t>), grid, dim3(64), 0, st, a);
             return;
         }
     }
