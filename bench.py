@@ -26,30 +26,103 @@ PEAK_INT8_TOPS = 5000.0  # MI355X dense INT8 MFMA, published: 5.0 POP/s
 PEAK_BF16_TFLOPS = 2500.0
 
 
-def recorded_traffic(workload: str):
-    """HBM bytes per launch of the attention kernel, as recorded from the rocprofv3 FETCH_SIZE /
-    WRITE_SIZE runs summarised under profiles/ (None if no summary exists for this workload)."""
-    import re
+def attention_kernel_symbol(w):
+    """(mangled symbol, demangled name as the profiler prints it, wavefronts per row-block visit, wavefronts per SIMD)
+    of the kernel that paro_sparse_attn launches for an integer workload."""
+    t, tn = ("t", "unsigned short") if w.dtype == "bf16" else ("f", "float")
+    if w.block == 64 and w.d == 64 and w.bits_qk == 8:
+        return ("_ZN4paro18attn_i8_w64_kernelILi%dE%sEEvNS_8AttnArgsE" % (w.bits_pv, t),
+                "paro::attn_i8_w64_kernel<%d, %s>" % (w.bits_pv, tn), 1, 2)
+    return ("_ZN4paro14attn_i8_kernelILi%dELi%dELi%dELi%dE%sLi0EEEvNS_8AttnArgsE" % (w.block, w.d, w.bits_qk, w.bits_pv, t),
+            "paro::attn_i8_kernel<%d, %d, %d, %d, %s, 0>" % (w.block, w.d, w.bits_qk, w.bits_pv, tn), w.block // 32, 3 if w.d == 64 else 2)
 
-    path = os.path.join(ROOT, "profiles", "hot_path_%s_hbm_traffic.md" % workload)
+
+def static_loop_counts(w):
+    """Vector instructions per loop iteration (one visit of a live block by one wavefront) of the built attention
+    kernel, by issue class, from the compiler's listing (lib/attn_loop_counts.json, written by the build).  Of the
+    kernel's loop variants the one with the fewest instructions is the folded-exponent form that 8-bit P codes take."""
+    path = os.path.join(ROOT, "paper_2506_16054_amd", "lib", "attn_loop_counts.json")
     try:
-        m = re.search(r"traffic_bytes_per_launch paro_sparse_attn %s = (\d+)" % re.escape(workload), open(path).read())
-        return int(m.group(1)) if m else None
+        loops = json.load(open(path)).get(attention_kernel_symbol(w)[0])
     except OSError:
         return None
+    if not loops:
+        return None
+    return min(loops, key=lambda c: sum(c.values()))
 
 
-def recorded_valu_instructions(workload: str):
-    """Vector-ALU wave instructions per launch of the attention kernel (rocprofv3 SQ_INSTS_VALU, summarised
-    under profiles/), or None."""
+def recorded_counters(w, live_blocks):
+    """SQ_INSTS_VALU per launch of the attention kernel and HBM bytes per launch, as recorded from rocprofv3 runs
+    summarised under profiles/ - but only if that record is of the kernel this build launches: the summary must
+    name the same kernel and its instruction count must agree (3 %) with the built kernel's loop.  Otherwise the
+    record is reported as stale and not used."""
     import re
 
-    path = os.path.join(ROOT, "profiles", "attn_i8_%s_sq_counters.md" % workload)
+    out = {"valu_instructions": None, "traffic": None, "stale": None}
+    _, name, waves, _ = attention_kernel_symbol(w)
+    static = static_loop_counts(w)
+    path = os.path.join(ROOT, "profiles", "attn_i8_%s_sq_counters.md" % w.name)
     try:
-        m = re.search(r"\| SQ_INSTS_VALU \| ([0-9.e+]+) \|", open(path).read())
-        return float(m.group(1)) if m else None
+        text = open(path).read()
+        m = re.search(r"\| SQ_INSTS_VALU \| ([0-9.e+]+) \|", text)
+        if m and static:
+            measured = float(m.group(1))
+            expected = sum(static.values()) * live_blocks * waves
+            out["stale"] = name not in text or abs(measured / expected - 1.0) > 0.03
+            if not out["stale"]:
+                out["valu_instructions"] = measured
     except OSError:
+        pass
+    path = os.path.join(ROOT, "profiles", "hot_path_%s_hbm_traffic.md" % w.name)
+    try:
+        text = open(path).read()
+        m = re.search(r"traffic_bytes_per_launch paro_sparse_attn %s = (\d+)" % re.escape(w.name), text)
+        if m and name in text:
+            out["traffic"] = int(m.group(1))
+    except OSError:
+        pass
+    return out
+
+
+PROBE_OF_CLASS = {"fma": "v_fma_f32", "add_mul": "v_add_f32", "int_simple": "v_add_u32", "half_rate": "v_max3_i32",
+                  "transcendental": "v_exp_f32", "permlane_swap": "v_permlane32_swap_b32", "mfma": "v_mfma_i32_32x32x32_i8"}
+
+
+def valu_issue_roofline(w, live_blocks, attn_ms, n_cus):
+    """What binds the integer attention kernels: instruction issue.  Model time = sum over issue classes of
+    (instructions of the class per loop iteration, from the compiler's listing) x (what one such wavefront
+    instruction costs a SIMD, measured now by the issue probe at the kernel's occupancy, in nanoseconds at the clock
+    the probe's load runs at) x iterations / SIMDs.  frac = model / measured: 1 means the kernel runs at the summed
+    issue cost of its own instructions with nothing hidden and nothing lost."""
+    from paper_2506_16054_amd import probe
+
+    static = static_loop_counts(w)
+    if not static:
         return None
+    _, name, waves, occupancy = attention_kernel_symbol(w)
+    kinds = probe.kinds()
+    cost_cycles, cost_ns = {}, {}
+    for cls in static:
+        cyc, ghz, _ = probe.issue_cost(kinds.index(PROBE_OF_CLASS[cls]), occupancy)
+        cost_cycles[cls], cost_ns[cls] = cyc, cyc / ghz
+    iterations = live_blocks * waves
+    simds = 4 * n_cus
+    model_ms = sum(static[c] * cost_ns[c] for c in static) * iterations / simds * 1e-6
+    model_no_mfma_ms = sum(static[c] * cost_ns[c] for c in static if c != "mfma") * iterations / simds * 1e-6
+    return {
+        "bound": "valu_issue",
+        "kernel": name,
+        "frac": model_ms / attn_ms,
+        "frac_vector_only": model_no_mfma_ms / attn_ms,
+        "model_ms": model_ms,
+        "measured_ms": attn_ms,
+        "instructions_per_iteration": static,
+        "cost_cycles_per_wave_instruction": {k: round(v, 2) for k, v in cost_cycles.items()},
+        "wavefronts_per_simd": occupancy,
+        "iterations_per_launch": iterations,
+        "note": "iteration = one live block visited by one wavefront; costs from lib/libparo_probe.so in this run; "
+                "frac_vector_only leaves the matrix instructions out (they overlap with vector work only in part)",
+    }
 
 
 def parse():
@@ -97,6 +170,8 @@ def cpu_baseline(w, perm_ids, row_ptr, col_idx, target_seconds):
         threadpool_limits(1)
     except Exception:
         pass
+    # at most 16 worker processes: that is the CPU share of one GPU on the benchmark boxes, whatever the
+    # affinity mask shows
     cores = max(1, min(len(os.sched_getaffinity(0)), 16, w.k))
     heads_done, live_done = 0, 0
     t_prep = t_attn = 0.0
@@ -129,7 +204,8 @@ def cpu_baseline(w, perm_ids, row_ptr, col_idx, target_seconds):
         "unit": "dense-equivalent TOPS",
         "cores": cores,
         "kind": "oracle",
-        "sample": "heads 0..%d of %d of %s (%d live blocks): attention %.1f s on %d processes, reorder+quantize %.1f s on 1"
+        "sample": "heads 0..%d of %d of %s (%d live blocks): attention %.1f s on %d processes (capped at 16, one GPU's CPU share "
+                  "on the box), reorder+quantize %.1f s on 1; block list from the library's host routine (bit-identical to the oracle's)"
                   % (heads_done - 1, w.nh, w.name, live_done, t_attn, cores, t_prep),
     }
 
@@ -315,7 +391,9 @@ def main():
     from paper_2506_16054_amd import probe
 
     sustained = probe.sustained_mfma_rate(8 if quantized else 16)
-    valu = recorded_valu_instructions(w.name) if quantized else None
+    rec = recorded_counters(w, live) if quantized else {"valu_instructions": None, "traffic": None, "stale": None}
+    n_cus = int(torch.cuda.get_device_properties(0).multi_processor_count)
+    issue = valu_issue_roofline(w, live, attn_avg, n_cus) if quantized else None
     out = {
         "metric": "dense_equivalent_TOPS",
         "value": dense_ops / (ms_per_step * 1e-3) / 1e12,
@@ -351,25 +429,18 @@ def main():
             "peak": peak,
             "unit": "TOP/s" if quantized else "TFLOP/s",
             "frac": achieved / peak,
-            "traffic": recorded_traffic(w.name),
-            "traffic_unit": "bytes per launch (HBM read + write, rocprofv3 counters scaled by a known copy)",
+            "traffic": rec["traffic"],
+            "traffic_unit": "bytes per launch (HBM read + write, rocprofv3 counters scaled by a known copy; null if profiles/ holds no record of the kernel this build launches)",
             "algorithmic_bytes": algorithmic_bytes,
             "peak_sustained": sustained,
             "frac_of_sustained": achieved / sustained,
             "peak_sustained_note": "rate of a kernel that only issues this matrix instruction, measured in this run",
         },
     }
-    if valu is not None:
-        # what actually binds the kernel at d = 64: vector-ALU issue.  Peak: 157.3 TFLOP/s of fp32 vector
-        # math = 2 flop x 64 lanes per wave instruction -> 1.229e12 wave instructions per second.
-        peak_wave_inst = 157.3e12 / 128.0
-        out["valu_issue"] = {
-            "wave_instructions_per_launch": valu,
-            "achieved_per_s": valu / (attn_avg * 1e-3),
-            "peak_per_s": peak_wave_inst,
-            "frac": valu / (attn_avg * 1e-3) / peak_wave_inst,
-            "note": "instruction count from profiles/ (SQ_INSTS_VALU); exp2, conversions and cross-lane moves issue at 1/2 to 1/4 of the fp32 rate",
-        }
+    if issue is not None:
+        issue["recorded_SQ_INSTS_VALU_per_launch"] = rec["valu_instructions"]
+        issue["profiles_record_stale"] = rec["stale"]
+        out["roofline_valu_issue"] = issue
     if prefetch is not None:
         out["mask_prefetch"] = prefetch
     if cpu is not None:

@@ -68,6 +68,83 @@ def _compile(src: str, extra, objdir: str = LIBDIR) -> str:
     return obj
 
 
+# ---- static instruction counts of the attention kernels' block loops (read by bench.py) --------------------
+_RARE = 24  # a loop block with this many v_cndmask or v_mul is a rarely taken branch (ragged-tail masking, re-referencing)
+
+
+def instruction_class(op: str) -> str:
+    """Issue class of a vector instruction mnemonic, as priced by the instruction-issue probe."""
+    op = re.sub(r"_(e32|e64|dpp|sdwa)$", "", op)
+    if "mfma" in op:
+        return "mfma"
+    if op in ("v_exp_f32", "v_rcp_f32", "v_log_f32", "v_rsq_f32", "v_sqrt_f32", "v_exp_f16"):
+        return "transcendental"
+    if op.startswith("v_permlane"):
+        return "permlane_swap"
+    if op in ("v_fma_f32", "v_fmac_f32", "v_fmamk_f32", "v_fmaak_f32"):
+        return "fma"
+    if op in ("v_add_f32", "v_sub_f32", "v_subrev_f32", "v_mul_f32"):
+        return "add_mul"
+    if op in ("v_add_u32", "v_sub_u32", "v_subrev_u32", "v_and_b32", "v_or_b32", "v_xor_b32", "v_mov_b32", "v_lshlrev_b32", "v_lshrrev_b32"):
+        return "int_simple"
+    return "half_rate"  # max/min, conversions, byte permute, cross-lane moves, 64-bit address arithmetic, ...
+
+
+def loop_instruction_counts(asm: str) -> dict:
+    """{kernel symbol: [ {class: count per loop iteration}, ... one entry per innermost loop that holds matrix
+    instructions ]} from the compiler's assembly listing.  Loop blocks that are rarely taken branches are left out."""
+    out = {}
+    for m in re.finditer(r"^(_ZN4paro\w*attn\w+):[^\n]*\n(.*?)\n\s*s_endpgm", asm, re.S | re.M):
+        name, body = m.group(1), m.group(2)
+        loops, label, header = {}, None, None
+        for line in body.split("\n"):
+            t = line.strip()
+            lm = re.match(r"^(\.LBB\d+_\d+):\s*(;.*)?$", t)
+            if lm:
+                label, note = lm.group(1), lm.group(2) or ""
+                hm = re.search(r"Header=(BB\d+_\d+)", note)
+                header = "." + "L" + hm.group(1) if hm else (label if "Loop Header" in note else None)
+                if header:
+                    loops.setdefault(header, []).append([])
+                continue
+            if header and t and not t.startswith(";") and not t.startswith("."):
+                op = t.split()[0]
+                if op.startswith("v_"):
+                    loops[header][-1].append(op)
+                elif op.startswith("s_cbranch") or op == "s_branch":
+                    loops[header].append([])  # what follows a branch is another basic block
+        entries = []
+        for blocks in loops.values():
+            counts = {}
+            for ops in blocks:
+                if sum(o.startswith("v_cndmask") for o in ops) >= _RARE or sum(o.startswith("v_mul_f32") for o in ops) >= _RARE:
+                    continue
+                for o in ops:
+                    c = instruction_class(o)
+                    counts[c] = counts.get(c, 0) + 1
+            if counts.get("mfma"):
+                entries.append(counts)
+        if entries:
+            out[name] = entries
+    return out
+
+
+def write_loop_counts(extra, objdir: str) -> str:
+    import json
+
+    asm_path = os.path.join(objdir, "sparse_attn.s")
+    cmd = [hipcc(), *HIPCC_FLAGS, *extra, "-S", "--cuda-device-only", os.path.join(CSRC, "sparse_attn.hip"), "-o", asm_path]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc -S failed on sparse_attn.hip:\n%s" % r.stderr)
+    counts = loop_instruction_counts(open(asm_path).read())
+    os.remove(asm_path)
+    path = os.path.join(objdir, "attn_loop_counts.json")
+    with open(path, "w") as f:
+        json.dump(counts, f, indent=1, sort_keys=True)
+    return path
+
+
 def _link(out: str, objs) -> None:
     cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -82,7 +159,9 @@ def build_library(extra_flags=(), verbose: bool = True, out: str = LIBPATH, prob
     os.makedirs(objdir, exist_ok=True)
     srcs = SOURCES + (PROBE_SOURCES if probe_out else ())
     with ThreadPoolExecutor(max_workers=4) as ex:
+        counts = ex.submit(write_loop_counts, list(extra_flags), objdir)
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags), objdir), srcs))
+        counts.result()
     _link(out, objs[: len(SOURCES)])
     if probe_out:
         os.makedirs(os.path.dirname(probe_out), exist_ok=True)
