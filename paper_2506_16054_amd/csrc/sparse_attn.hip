@@ -493,27 +493,35 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
         } else {
             w_blk = __builtin_amdgcn_exp2f(w_base - off_n);
         }
+        // All exponentials of the block first (in place of the raw logits), then the row sum as four independent
+        // chains and the conversions: neighbouring instructions do not wait for each other's results.
+        float ev[KT][16];
 #pragma unroll
-        for (int T = 0; T < KT; ++T) {
+        for (int T = 0; T < KT; ++T)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                ev[T][r] = __builtin_amdgcn_exp2f(fmaf(FOLD ? __int_as_float(sacc[T][r]) : int_result(sacc[T][r]), c, off_f));
+                if constexpr (TAIL) {
+                    if (32 * T + 8 * (r >> 2) + 4 * g + (r & 3) >= a.n_tokens - (a.kblocks - 1) * BLK) ev[T][r] = 0.0f;
+                }
+            }
+        float part_sum[4];
+#pragma unroll
+        for (int T = 0; T < KT; ++T)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) part_sum[r & 3] = (T == 0 && r < 4) ? ev[T][r] : part_sum[r & 3] + ev[T][r];
+        rs = (part_sum[0] + part_sum[1]) + (part_sum[2] + part_sum[3]);
+#pragma unroll
+        for (int T = 0; T < KT; ++T)
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
-                float ev[4];
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    ev[p] = __builtin_amdgcn_exp2f(fmaf(FOLD ? __int_as_float(sacc[T][4 * qd + p]) : int_result(sacc[T][4 * qd + p]), c, off_f));
-                    if constexpr (TAIL) {
-                        if (32 * T + 8 * qd + 4 * g + p >= a.n_tokens - (a.kblocks - 1) * BLK) ev[p] = 0.0f;
-                    }
-                    rs = (T == 0 && qd == 0 && p == 0) ? ev[p] : rs + ev[p];
-                }
                 // (the builtin, not inline assembly: the instruction consumes results of the
                 // transcendental unit, and only instructions the compiler can see get the wait state
                 // that this needs when they follow the exponential directly)
-                const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[0], ev[1]));
-                const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[2], ev[3]));
+                const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[T][4 * qd], ev[T][4 * qd + 1]));
+                const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[T][4 * qd + 2], ev[T][4 * qd + 3]));
                 pf[T][qd] = (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u);
             }
-        }
         l = fmaf(rs, w_blk, l);  // rs carries the factor 1/65535; it is undone once, at the end
 
         // ---- O^T += (sP sv_j 2^(m' - m_ref)) V_j^T P^T
@@ -811,21 +819,27 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
             } else {
                 w_blk = __builtin_amdgcn_exp2f(w_base[H] - off_n);
             }
-            // ---- E, row sum, codes packed as B operand
-            float rs = 0.0f;
+            // ---- E (all of the half first, in place of the raw logits), row sum as four independent chains,
+            // codes packed as B operand
+            float ev[2][16];
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    ev[T][r] = __builtin_amdgcn_exp2f(fmaf(FOLD ? __int_as_float(sacc[H][T][r]) : int_result(sacc[H][T][r]), c, off_f));
+            float part_sum[4];
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) part_sum[r & 3] = (T == 0 && r < 4) ? ev[T][r] : part_sum[r & 3] + ev[T][r];
+            const float rs = (part_sum[0] + part_sum[1]) + (part_sum[2] + part_sum[3]);
             v4i pf[2];
 #pragma unroll
             for (int T = 0; T < 2; ++T)
 #pragma unroll
                 for (int qd = 0; qd < 4; ++qd) {
-                    float ev[4];
-#pragma unroll
-                    for (int p = 0; p < 4; ++p) {
-                        ev[p] = __builtin_amdgcn_exp2f(fmaf(FOLD ? __int_as_float(sacc[H][T][4 * qd + p]) : int_result(sacc[H][T][4 * qd + p]), c, off_f));
-                        rs = (T == 0 && qd == 0 && p == 0) ? ev[p] : rs + ev[p];
-                    }
-                    const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[0], ev[1]));
-                    const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[2], ev[3]));
+                    const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[T][4 * qd], ev[T][4 * qd + 1]));
+                    const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[T][4 * qd + 2], ev[T][4 * qd + 3]));
                     pf[T][qd] = (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u);
                 }
             l[H] = fmaf(rs, w_blk, l[H]);
