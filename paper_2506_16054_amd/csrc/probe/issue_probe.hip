@@ -279,26 +279,37 @@ __global__ __launch_bounds__(1024) void block_kernel(int iters, WaveTimes* __res
         const float ymax = c * (__int_as_float(mx) - 12582912.0f);
         m = fmaxf(m, ymax);
         const float off = -9.0f - m - c * 12582912.0f;
-        float rs = 0.0f;
+        // as in the product kernel: all exponentials first, the row sum as four chains, then the conversions
+        float ev[2][16];
+#pragma unroll
+        for (int T = 0; T < 2; ++T)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                ev[T][r] = fmaf(__int_as_float(s[T][r]), c, off);
+                if constexpr (PARTS & 2) ev[T][r] = __builtin_amdgcn_exp2f(ev[T][r]);
+            }
+        float part_sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if constexpr (PARTS & 32) {
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) part_sum[r & 3] += ev[T][r];
+        } else {
+            part_sum[0] = ev[0][0];
+        }
+        const float rs = (part_sum[0] + part_sum[1]) + (part_sum[2] + part_sum[3]);
         v4i pf[2];
 #pragma unroll
         for (int T = 0; T < 2; ++T)
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
-                float ev[4];
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    ev[p] = fmaf(__int_as_float(s[T][4 * qd + p]), c, off);
-                    if constexpr (PARTS & 2) ev[p] = __builtin_amdgcn_exp2f(ev[p]);
-                    if constexpr (PARTS & 32) rs += ev[p];
-                    else if (p == 0 && qd == 0) rs += ev[p];
-                }
                 if constexpr (PARTS & 4) {
-                    const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[0], ev[1]));
-                    const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[2], ev[3]));
+                    const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[T][4 * qd], ev[T][4 * qd + 1]));
+                    const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[T][4 * qd + 2], ev[T][4 * qd + 3]));
                     pf[T][qd] = (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u);
                 } else {
-                    pf[T][qd] = __float_as_int(ev[0]) ^ __float_as_int(ev[1]) ^ __float_as_int(ev[2]) ^ __float_as_int(ev[3]);
+                    pf[T][qd] = __float_as_int(ev[T][4 * qd]) ^ __float_as_int(ev[T][4 * qd + 1]) ^ __float_as_int(ev[T][4 * qd + 2]) ^
+                                __float_as_int(ev[T][4 * qd + 3]);
                 }
             }
         l = fmaf(rs, 0.5f, l);
