@@ -103,7 +103,7 @@ def valu_issue_roofline(w, live_blocks, attn_ms, n_cus):
     kinds = probe.kinds()
     cost_cycles, cost_ns = {}, {}
     for cls in static:
-        cyc, ghz, _ = probe.issue_cost(kinds.index(PROBE_OF_CLASS[cls]), occupancy)
+        cyc, ghz = probe.issue_cost(kinds.index(PROBE_OF_CLASS[cls]), occupancy)[:2]
         cost_cycles[cls], cost_ns[cls] = cyc, cyc / ghz
     iterations = live_blocks * waves
     simds = 4 * n_cus

@@ -78,14 +78,17 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int seed, in
 enum Kind {
     K_FMA_F32 = 0, K_ADD_F32, K_MUL_F32, K_MAX3_I32, K_CVT_PKNORM_U16, K_PERM_B32, K_EXP_F32, K_CVT_F32_I32,
     K_PK_FMA_F16, K_PK_ADD_F16, K_EXP_F16, K_FMA_MIXLO_F16, K_DOT2_F32_F16, K_CVT_PKRTZ_F16, K_MOV_DPP, K_PERMLANE32_SWAP,
-    K_CNDMASK, K_ADD_U32, K_LSHL_OR, K_MFMA_I8_32, K_MFMA_I8_16, K_SOFTMAX_MIX, K_COUNT
+    K_CNDMASK, K_ADD_U32, K_LSHL_OR, K_MFMA_I8_32, K_MFMA_I8_16, K_SOFTMAX_MIX,
+    K_MFMA_WITH_ADD, K_MFMA_WITH_FMA, K_MFMA_WITH_EXP, K_MFMA_WITH_MIX, K_COUNT
 };
 
 const char* const kKindNames[K_COUNT] = {
     "v_fma_f32", "v_add_f32", "v_mul_f32", "v_max3_i32", "v_cvt_pknorm_u16_f32", "v_perm_b32", "v_exp_f32", "v_cvt_f32_i32",
     "v_pk_fma_f16", "v_pk_add_f16", "v_exp_f16", "v_fma_mixlo_f16", "v_dot2_f32_f16", "v_cvt_pkrtz_f16_f32", "v_mov_b32 dpp quad_perm",
     "v_permlane32_swap_b32", "v_cndmask_b32", "v_add_u32", "v_lshl_or_b32", "v_mfma_i32_32x32x32_i8", "v_mfma_i32_16x16x64_i8",
-    "softmax mix (fma, exp, add, 1/2 cvt_pknorm, 1/4 perm, 1/2 max3)"};
+    "softmax mix (fma, exp, add, 1/2 cvt_pknorm, 1/4 perm, 1/2 max3)",
+    "one wavefront: 4 x (v_mfma_i32_32x32x32_i8 + 12 v_add_f32), per 32 = 1/8 of that", "one wavefront: 4 x (mfma + 12 v_fma_f32), per 32",
+    "one wavefront: 4 x (mfma + 4 v_exp_f32), per 32", "one wavefront: 4 x (mfma + 2 x (fma, exp, add) + max3), per 32"};
 
 #define PROBE_REP8(X) X(0) X(1) X(2) X(3) X(4) X(5) X(6) X(7)
 
@@ -144,6 +147,17 @@ __device__ inline void issue_body(float (&f)[8], int (&n)[8], float a, float b, 
         for (int r = 0; r < kUnroll; ++r) c[r & 3] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ma, mb, c[r & 3], 0, 0, 0);
 #pragma unroll
         for (int r = 0; r < 4; ++r) { acc[r][0] = c[r][0]; acc[r][1] = c[r][1]; acc[r][2] = c[r][2]; acc[r][3] = c[r][3]; }
+    } else if constexpr (KIND == K_MFMA_WITH_ADD || KIND == K_MFMA_WITH_FMA || KIND == K_MFMA_WITH_EXP || KIND == K_MFMA_WITH_MIX) {
+        // a wavefront's own matrix instructions among its own, independent vector instructions:
+        // four groups of one matrix instruction (its own accumulator) and about 30 cycles of vector work
+#define GROUP(r)                                                                                           \
+        acc[r] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ma, mb, acc[r], 0, 0, 0);                               \
+        if constexpr (KIND == K_MFMA_WITH_ADD) { PROBE_REP8(ADD) ADD(0) ADD(1) ADD(2) ADD(3) }                 \
+        else if constexpr (KIND == K_MFMA_WITH_FMA) { PROBE_REP8(FMA) FMA(0) FMA(1) FMA(2) FMA(3) }            \
+        else if constexpr (KIND == K_MFMA_WITH_EXP) { EXP(2 * r) EXP(2 * r + 1) EXP((2 * r + 4) & 7) EXP((2 * r + 5) & 7) } \
+        else { FMA(2 * r) FMA(2 * r + 1) EXP(2 * r) EXP(2 * r + 1) ADD(2 * r) ADD(2 * r + 1) MAX3(r) }
+        GROUP(0) GROUP(1) GROUP(2) GROUP(3)
+#undef GROUP
     } else {
         // the per-logit sequence of the attention kernel, 8 logits per round, 32 instructions:
         // 8 x (fma, exp, add) + 4 cvt_pknorm + 2 perm + 2 max3  (the last two instructions pad to 32 with max3)
@@ -343,6 +357,208 @@ __global__ __launch_bounds__(1024) void block_kernel(int iters, WaveTimes* __res
     }
 }
 
+// ---- two independent halves of a block per wavefront, matrix instructions of one half issued among the vector
+// work of the other (MODE 1) or everything in program order (MODE 0) -----------------------------------------------
+// One iteration = one 64-query x 64-key visit = two half-blocks of the replica above.  MODE 1 orders the work as
+//   QK(0) | QK(1) among softmax(0) | PV(0) among softmax(1) | PV(1) among update(0) | update(1)
+// and pins that order with scheduling barriers, to measure whether a wavefront's own matrix instructions run in
+// the shadow of its own vector instructions.  MODE 2 additionally moves QK(0) of the next visit among update(1).
+template <int MODE>
+__global__ __launch_bounds__(256) void pair_kernel(int iters, WaveTimes* __restrict__ out, int* __restrict__ sink) {
+    const int wave = threadIdx.x >> 6;
+    const int waves = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63;
+    v4i kf[2] = {{lane, 2, 3, 4}, {lane + 1, 5, 3, 4}}, vf[2] = {{lane, 9, 1, 2}, {lane + 3, 9, 7, 2}};
+    v4i qf[2] = {{5, 6, 7, lane}, {lane, 1, 7, 3}};
+    asm volatile("" : "+v"(kf[0]), "+v"(kf[1]), "+v"(vf[0]), "+v"(vf[1]), "+v"(qf[0]), "+v"(qf[1]));
+    v16i init;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) init[r] = 0x4B400000;
+    asm volatile("" : "+v"(init));
+    float acc[2][2][16];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int d = 0; d < 2; ++d)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[h][d][r] = 0.0f;
+    float m[2] = {-1e30f, -1e30f}, l[2] = {0.0f, 0.0f}, w[2] = {0.0f, 0.0f};
+    const float c = 3.0e-4f;
+    v16i s[2][2], o[2][2];
+    v4i pf[2][2];
+
+#define PAIR_QK(h)                                                                      \
+    _Pragma("unroll") for (int T = 0; T < 2; ++T) {                                     \
+        s[h][T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[T], qf[h], init, 0, 0, 0);    \
+        s[h][T] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[1 - T], qf[h], s[h][T], 0, 0, 0); \
+    }
+#define PAIR_PV(h)                                                                      \
+    _Pragma("unroll") for (int d = 0; d < 2; ++d) {                                     \
+        o[h][d] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[d], pf[h][0], init, 0, 0, 0); \
+        o[h][d] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[1 - d], pf[h][1], o[h][d], 0, 0, 0); \
+    }
+#define PAIR_SOFTMAX(h)                                                                 \
+    {                                                                                   \
+        int part[4] = {0, 0, 0, 0};                                                     \
+        _Pragma("unroll") for (int T = 0; T < 2; ++T)                                   \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) part[r & 3] = max(part[r & 3], s[h][T][r]); \
+        const int mx = max(max(part[0], part[1]), max(part[2], part[3]));               \
+        const float ymax = c * (__int_as_float(mx) - 12582912.0f);                      \
+        m[h] = fmaxf(m[h], ymax);                                                       \
+        const float off = -9.0f - m[h] - c * 12582912.0f;                               \
+        float ev[2][16];                                                                \
+        _Pragma("unroll") for (int T = 0; T < 2; ++T)                                   \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r)                                  \
+            ev[T][r] = __builtin_amdgcn_exp2f(fmaf(__int_as_float(s[h][T][r]), c, off)); \
+        float part_sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};                                   \
+        _Pragma("unroll") for (int T = 0; T < 2; ++T)                                   \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) part_sum[r & 3] += ev[T][r];     \
+        const float rs = (part_sum[0] + part_sum[1]) + (part_sum[2] + part_sum[3]);     \
+        _Pragma("unroll") for (int T = 0; T < 2; ++T)                                   \
+        _Pragma("unroll") for (int qd = 0; qd < 4; ++qd) {                              \
+            const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[T][4 * qd], ev[T][4 * qd + 1])); \
+            const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[T][4 * qd + 2], ev[T][4 * qd + 3])); \
+            pf[h][T][qd] = (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u);             \
+        }                                                                               \
+        l[h] = fmaf(rs, 0.5f, l[h]);                                                    \
+        w[h] = 1.0f / (1.0f + l[h]);                                                    \
+    }
+#define PAIR_UPDATE(h)                                                                  \
+    _Pragma("unroll") for (int d = 0; d < 2; ++d)                                       \
+    _Pragma("unroll") for (int r = 0; r < 16; ++r)                                      \
+        acc[h][d][r] = fmaf(__int_as_float(o[h][d][r]) - 12582912.0f, w[h], acc[h][d][r]);
+// the region since the last full barrier is scheduled as `groups` x (1 matrix instruction, `valu` vector instructions)
+#define PAIR_INTERLEAVE(valu)                                                           \
+    _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                     \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                              \
+        __builtin_amdgcn_sched_group_barrier(0x002, valu, 0);                           \
+    }
+#define PAIR_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// the same work in pieces, for MODE 3: one matrix instruction in front of each run of 8 x (logit fma, exp2)
+#define PAIR_QK1(h, i)                                                                  \
+    s[h][(i) >> 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[((i) >> 1) ^ ((i) & 1)], qf[h], ((i) & 1) ? s[h][(i) >> 1] : init, 0, 0, 0);
+#define PAIR_PV1(h, i)                                                                  \
+    o[h][(i) >> 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf[((i) >> 1) ^ ((i) & 1)], pf[h][(i) & 1], ((i) & 1) ? o[h][(i) >> 1] : init, 0, 0, 0);
+#define PAIR_SM_HEAD(h)                                                                 \
+    {                                                                                   \
+        int part[4] = {0, 0, 0, 0};                                                     \
+        _Pragma("unroll") for (int T = 0; T < 2; ++T)                                   \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) part[r & 3] = max(part[r & 3], s[h][T][r]); \
+        const int mx = max(max(part[0], part[1]), max(part[2], part[3]));               \
+        const float ymax = c * (__int_as_float(mx) - 12582912.0f);                      \
+        m[h] = fmaxf(m[h], ymax);                                                       \
+        off = -9.0f - m[h] - c * 12582912.0f;                                           \
+    }
+#define PAIR_SM_EXP(h, g)                                                               \
+    _Pragma("unroll") for (int r = 0; r < 8; ++r)                                       \
+        ev[(g) >> 1][8 * ((g) & 1) + r] = __builtin_amdgcn_exp2f(fmaf(__int_as_float(s[h][(g) >> 1][8 * ((g) & 1) + r]), c, off));
+#define PAIR_SM_TAIL(h)                                                                 \
+    {                                                                                   \
+        float part_sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};                                   \
+        _Pragma("unroll") for (int T = 0; T < 2; ++T)                                   \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) part_sum[r & 3] += ev[T][r];     \
+        const float rs = (part_sum[0] + part_sum[1]) + (part_sum[2] + part_sum[3]);     \
+        _Pragma("unroll") for (int T = 0; T < 2; ++T)                                   \
+        _Pragma("unroll") for (int qd = 0; qd < 4; ++qd) {                              \
+            const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[T][4 * qd], ev[T][4 * qd + 1])); \
+            const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[T][4 * qd + 2], ev[T][4 * qd + 3])); \
+            pf[h][T][qd] = (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u);             \
+        }                                                                               \
+        l[h] = fmaf(rs, 0.5f, l[h]);                                                    \
+        w[h] = 1.0f / (1.0f + l[h]);                                                    \
+    }
+// matrix instruction first, then the piece's vector instructions
+#define PAIR_MFMA_FIRST()                                                               \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  \
+    __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);                                 \
+    PAIR_FENCE();
+    float off = 0.0f;
+    float ev[2][16];
+
+    const long long c0 = __builtin_readcyclecounter();
+    const long long t0 = wall_clock64();
+    if constexpr (MODE == 2) { PAIR_QK(0) PAIR_FENCE(); }
+    for (int it = 0; it < iters; ++it) {
+        if constexpr (MODE == 3 || MODE == 4) {
+            // MODE 4: the same pieces in the same order without the matrix instructions moved in (they run as two
+            // groups of four in front of each softmax), as the reference for MODE 3
+            PAIR_QK(0) PAIR_FENCE();
+            if constexpr (MODE == 4) { PAIR_QK(1) PAIR_FENCE(); }
+            PAIR_SM_HEAD(0) PAIR_FENCE();
+            if constexpr (MODE == 3) {
+                PAIR_QK1(1, 0) PAIR_SM_EXP(0, 0) PAIR_MFMA_FIRST() PAIR_QK1(1, 1) PAIR_SM_EXP(0, 1) PAIR_MFMA_FIRST()
+                PAIR_QK1(1, 2) PAIR_SM_EXP(0, 2) PAIR_MFMA_FIRST() PAIR_QK1(1, 3) PAIR_SM_EXP(0, 3) PAIR_MFMA_FIRST()
+            } else {
+                PAIR_SM_EXP(0, 0) PAIR_FENCE(); PAIR_SM_EXP(0, 1) PAIR_FENCE(); PAIR_SM_EXP(0, 2) PAIR_FENCE(); PAIR_SM_EXP(0, 3) PAIR_FENCE();
+            }
+            PAIR_SM_TAIL(0) PAIR_FENCE();
+            if constexpr (MODE == 4) { PAIR_PV(0) PAIR_FENCE(); }
+            PAIR_SM_HEAD(1) PAIR_FENCE();
+            if constexpr (MODE == 3) {
+                PAIR_PV1(0, 0) PAIR_SM_EXP(1, 0) PAIR_MFMA_FIRST() PAIR_PV1(0, 1) PAIR_SM_EXP(1, 1) PAIR_MFMA_FIRST()
+                PAIR_PV1(0, 2) PAIR_SM_EXP(1, 2) PAIR_MFMA_FIRST() PAIR_PV1(0, 3) PAIR_SM_EXP(1, 3) PAIR_MFMA_FIRST()
+            } else {
+                PAIR_SM_EXP(1, 0) PAIR_FENCE(); PAIR_SM_EXP(1, 1) PAIR_FENCE(); PAIR_SM_EXP(1, 2) PAIR_FENCE(); PAIR_SM_EXP(1, 3) PAIR_FENCE();
+            }
+            PAIR_SM_TAIL(1) PAIR_FENCE();
+            PAIR_UPDATE(0) PAIR_FENCE();
+            PAIR_PV(1) PAIR_FENCE();
+            PAIR_UPDATE(1) PAIR_FENCE();
+        } else if constexpr (MODE == 0) {
+            PAIR_QK(0) PAIR_FENCE();
+            PAIR_SOFTMAX(0) PAIR_FENCE();
+            PAIR_PV(0) PAIR_FENCE();
+            PAIR_UPDATE(0) PAIR_FENCE();
+            PAIR_QK(1) PAIR_FENCE();
+            PAIR_SOFTMAX(1) PAIR_FENCE();
+            PAIR_PV(1) PAIR_FENCE();
+            PAIR_UPDATE(1) PAIR_FENCE();
+        } else {
+            if constexpr (MODE == 1) { PAIR_QK(0) PAIR_FENCE(); }
+            PAIR_QK(1) PAIR_SOFTMAX(0) PAIR_INTERLEAVE(48) PAIR_FENCE();
+            PAIR_PV(0) PAIR_SOFTMAX(1) PAIR_INTERLEAVE(48) PAIR_FENCE();
+            PAIR_PV(1) PAIR_UPDATE(0) PAIR_INTERLEAVE(16) PAIR_FENCE();
+            if constexpr (MODE == 1) {
+                PAIR_UPDATE(1) PAIR_FENCE();
+            }
+        }
+        kf[0][1] ^= it;
+        kf[1][2] += it;
+        if constexpr (MODE == 2) {
+            // QK(0) of the next visit among update(1) of this one (one visit too many at the end; its result is unused)
+            PAIR_FENCE();
+            PAIR_QK(0) PAIR_UPDATE(1) PAIR_INTERLEAVE(16) PAIR_FENCE();
+        }
+    }
+    const long long c1 = __builtin_readcyclecounter();
+    const long long t1 = wall_clock64();
+    float keep = l[0] + m[0] + l[1] + m[1];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int d = 0; d < 2; ++d)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) keep += acc[h][d][r];
+    if constexpr (MODE == 2) keep += (float)s[0][0][3];
+    if (lane == 0) {
+        out[blockIdx.x * waves + wave] = WaveTimes{c1 - c0, t1 - t0, c0, where_am_i()};
+        sink[blockIdx.x * waves + wave] = (int)keep;
+    }
+#undef PAIR_QK
+#undef PAIR_QK1
+#undef PAIR_PV1
+#undef PAIR_SM_HEAD
+#undef PAIR_SM_EXP
+#undef PAIR_SM_TAIL
+#undef PAIR_MFMA_FIRST
+#undef PAIR_PV
+#undef PAIR_SOFTMAX
+#undef PAIR_UPDATE
+#undef PAIR_INTERLEAVE
+#undef PAIR_FENCE
+}
+
 template <int KIND>
 int launch_issue(int cus, int w, int iters, int with_mfma, WaveTimes* out, int* sink, hipStream_t st) {
     if (with_mfma)
@@ -358,6 +574,13 @@ int launch_block(int cus, int w, int iters, WaveTimes* out, int* sink, hipStream
     hipLaunchKernelGGL(block_kernel<PARTS>, dim3(cus * w), dim3(256), lds_for(w), st, iters, out, sink);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? 0 : hip_failed("launch of block_kernel", e);
+}
+
+template <int MODE>
+int launch_pair(int cus, int iters, WaveTimes* out, int* sink, hipStream_t st) {
+    hipLaunchKernelGGL(pair_kernel<MODE>, dim3(cus * 2), dim3(256), lds_for(2), st, iters, out, sink);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? 0 : hip_failed("launch of pair_kernel", e);
 }
 
 }  // namespace
@@ -408,6 +631,7 @@ int paro_probe_issue(int kind, int cus, int waves_per_simd, int iters, int with_
         CASE(K_CVT_F32_I32) CASE(K_PK_FMA_F16) CASE(K_PK_ADD_F16) CASE(K_EXP_F16) CASE(K_FMA_MIXLO_F16) CASE(K_DOT2_F32_F16)
         CASE(K_CVT_PKRTZ_F16) CASE(K_MOV_DPP) CASE(K_PERMLANE32_SWAP) CASE(K_CNDMASK) CASE(K_ADD_U32) CASE(K_LSHL_OR)
         CASE(K_MFMA_I8_32) CASE(K_MFMA_I8_16) CASE(K_SOFTMAX_MIX)
+        CASE(K_MFMA_WITH_ADD) CASE(K_MFMA_WITH_FMA) CASE(K_MFMA_WITH_EXP) CASE(K_MFMA_WITH_MIX)
 #undef CASE
     }
     return rc < 0 ? rc : entries;
@@ -430,6 +654,24 @@ int paro_probe_block(int parts, int cus, int waves_per_simd, int iters, int64_t*
         CASE(63) CASE(62) CASE(61) CASE(59) CASE(55) CASE(47) CASE(31) CASE(0)
 #undef CASE
     }
+    return rc < 0 ? rc : entries;
+}
+
+// Enqueues the two-halves replica (see pair_kernel) with two wavefronts per SIMD on `cus` compute units:
+// mode 0 program order, 1 matrix instructions of one half among the vector work of the other, 2 as 1 plus the
+// next visit's first products among the last update.  Every wavefront runs `iters` visits = 2 * iters half-blocks.
+// Output as paro_probe_issue.
+int paro_probe_pair(int mode, int cus, int iters, int64_t* times, int32_t* sink, int64_t capacity, void* stream) {
+    if (mode < 0 || mode > 4 || cus < 1 || cus > 4096 || iters < 1 || iters > (1 << 20) || !times || !sink) return kErrInval;
+    const int entries = cus * 4 * 2;
+    if (capacity < entries) return kErrInval;
+    hipStream_t st = (hipStream_t)stream;
+    WaveTimes* out = (WaveTimes*)times;
+    const int rc = mode == 0   ? launch_pair<0>(cus, iters, out, sink, st)
+                   : mode == 1 ? launch_pair<1>(cus, iters, out, sink, st)
+                   : mode == 2 ? launch_pair<2>(cus, iters, out, sink, st)
+                   : mode == 3 ? launch_pair<3>(cus, iters, out, sink, st)
+                               : launch_pair<4>(cus, iters, out, sink, st);
     return rc < 0 ? rc : entries;
 }
 

@@ -601,9 +601,14 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? PARO_ATTN_WAVES_D64 : 2)) void 
 #define PARO_ATTN_SINGLE_WAVE 1
 #endif
 
-__device__ inline void lds_dma16(const uint8_t* src, uint8_t* lds_dst) {
-    // lane L's 16 bytes at src (per lane) land at lds_dst (wave-uniform) + 16 L
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src, (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
+// Lane L's 16 bytes at base + lane_off + OFFSET land at lds_dst + 16 L (lds_dst wave-uniform, lds_dst >= OFFSET
+// bytes into its array).  The instruction's immediate offset moves the global AND the LDS address, so the LDS
+// base is handed over OFFSET bytes low; the four or two requests of a tile then share one address register pair
+// instead of costing a per-lane 64-bit addition each.
+template <int OFFSET>
+__device__ inline void lds_dma16(const uint8_t* base, unsigned lane_off, uint8_t* lds_dst) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + lane_off),
+                                     (__attribute__((address_space(3))) void*)(lds_dst - OFFSET), 16, OFFSET, 0);
 }
 
 template <int PVBITS, typename OutT>
@@ -635,8 +640,10 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
     if (2 * cnt > a.kblocks) __builtin_amdgcn_s_setprio(2);
 
     const size_t head_rows = (size_t)bh * a.kblocks * BLK;
-    const uint8_t* kbase = a.k + head_rows * D + n * D + 16 * g;    // this lane's K fragment of key tile 0, step 0
-    const uint8_t* vbase = a.v + head_rows * D / VPACK + n * (BLK / VPACK) + 16 * g;  // this lane's V^T piece of channel tile 0
+    const uint8_t* kbase = a.k + head_rows * D;          // the head's K codes (wave-uniform)
+    const uint8_t* vbase = a.v + head_rows * D / VPACK;  // the head's V^T codes (wave-uniform)
+    const unsigned klane = n * D + 16 * g;               // this lane's K fragment of key tile 0, step 0, inside a block
+    const unsigned vlane = n * (BLK / VPACK) + 16 * g;   // this lane's V^T piece of channel tile 0, inside a block
     const float* skp = a.sk + (size_t)bh * a.kblocks;
     const float* svp = a.sv + (size_t)bh * a.kblocks;
     const float sq_i = a.sq[(size_t)bh * a.kblocks + i] * a.qk_scale;
@@ -662,20 +669,20 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
 
     // request the tiles of column block j into ring slot `slot`
     auto request = [&](int j, int slot) {
-        const uint8_t* kp = kbase + (size_t)j * (BLK * D);
+        const uint8_t* kp = kbase + (size_t)j * (BLK * D);  // j comes from a scalar register: kp, vp are wave-uniform
         const uint8_t* vp = vbase + (size_t)j * (BLK * D / VPACK);
-#pragma unroll
-        for (int T = 0; T < 2; ++T)
-#pragma unroll
-            for (int s = 0; s < 2; ++s) lds_dma16(kp + T * (32 * D) + 32 * s, &ring[slot][2 * T + s][0]);
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt) {
-            if constexpr (PVBITS == 4) {
-                lds_dma16(vp + dt * (32 * BLK / 2), &ring[slot][4 + dt][0]);
-            } else {
-#pragma unroll
-                for (int T = 0; T < 2; ++T) lds_dma16(vp + dt * (32 * BLK) + 32 * T, &ring[slot][4 + 2 * dt + T][0]);
-            }
+        lds_dma16<0>(kp, klane, &ring[slot][0][0]);
+        lds_dma16<32>(kp, klane, &ring[slot][1][0]);
+        lds_dma16<32 * D>(kp, klane, &ring[slot][2][0]);
+        lds_dma16<32 * D + 32>(kp, klane, &ring[slot][3][0]);
+        if constexpr (PVBITS == 4) {
+            lds_dma16<0>(vp, vlane, &ring[slot][4][0]);
+            lds_dma16<32 * BLK / 2>(vp, vlane, &ring[slot][5][0]);
+        } else {
+            lds_dma16<0>(vp, vlane, &ring[slot][4][0]);
+            lds_dma16<32>(vp, vlane, &ring[slot][5][0]);
+            lds_dma16<32 * BLK>(vp, vlane, &ring[slot][6][0]);
+            lds_dma16<32 * BLK + 32>(vp, vlane, &ring[slot][7][0]);
         }
     };
 

@@ -44,6 +44,7 @@ def lib() -> ctypes.CDLL:
         L.paro_probe_issue_name.argtypes = [i32]
         L.paro_probe_issue.argtypes = [i32, i32, i32, i32, i32, vp, vp, i64, vp]
         L.paro_probe_block.argtypes = [i32, i32, i32, i32, vp, vp, i64, vp]
+        L.paro_probe_pair.argtypes = [i32, i32, i32, vp, vp, i64, vp]
         _lib = L
     return _lib
 
@@ -112,9 +113,11 @@ def _times(launch, per_wave_work: float, timed_per_simd: int):
     hw = timed[:, 3] & 0xFFFFFFFF
     simd = ((timed[:, 3] >> 32) & 0xF) << 20 | (hw & 0xFFF0)
     last = {}
+    first = {}
     count = {}
     for key, c in zip(simd.tolist(), timed[:, 0].tolist()):
         last[key] = max(last.get(key, 0), c)
+        first[key] = min(first.get(key, c), c)
         count[key] = count.get(key, 0) + 1
     if set(count.values()) != {timed_per_simd}:
         raise RuntimeError("expected %d timed wavefronts on every SIMD, found %s" % (timed_per_simd, sorted(set(count.values()))))
@@ -125,7 +128,7 @@ def _times(launch, per_wave_work: float, timed_per_simd: int):
     mfma_rate = None
     if len(comp):
         mfma_rate = float(comp[:, 1].mean()) * 8.0 / cycles * 1000.0
-    return cycles / (per_wave_work * timed_per_simd), ghz, mfma_rate
+    return cycles / (per_wave_work * timed_per_simd), ghz, mfma_rate, float(np.median(list(first.values()))) / per_wave_work
 
 
 def issue_cost(kind: int, waves_per_simd: int, with_mfma: bool = False, iters: int = 8000):
@@ -141,25 +144,43 @@ def block_cost(parts: int, waves_per_simd: int, iters: int = 1500):
                   float(iters), waves_per_simd)
 
 
+PAIR_MODES = {
+    0: "program order: QK(0) softmax(0) PV(0) update(0) QK(1) softmax(1) PV(1) update(1)",
+    1: "QK(1) among softmax(0), PV(0) among softmax(1), PV(1) among update(0)",
+    2: "as 1, and QK(0) of the next visit among update(1)",
+    3: "one matrix instruction in front of every 8 x (logit fma, exp2): QK(1) in softmax(0), PV(0) in softmax(1)",
+    4: "the pieces of 3 in the same order, matrix instructions not moved in",
+}
+
+
+def pair_cost(mode: int, iters: int = 1500):
+    """(shader cycles per half-block per SIMD of the two-halves replica, two wavefronts per SIMD, clock, None, first)."""
+    return _times(lambda t, s, cap: lib().paro_probe_pair(mode, compute_units(), iters, t, s, cap, _stream()), 2.0 * iters, 2)
+
+
 def issue_table() -> dict:
     """All measurements behind profiles/valu_issue_costs.md as a dictionary."""
     names = kinds()
     single = {name: {w: issue_cost(k, w) for w in (2, 3, 4)} for k, name in enumerate(names)}
-    beside = {name: issue_cost(k, 4, with_mfma=True) for k, name in enumerate(names) if not name.startswith("v_mfma")}
+    beside = {name: issue_cost(k, 4, with_mfma=True) for k, name in enumerate(names) if "mfma" not in name}
     blocks = {label: {w: block_cost(parts, w) for w in (2, 3, 4)} for label, parts in BLOCK_PARTS.items()}
-    return {"single": single, "beside_mfma": beside, "block": blocks}
+    pairs = {label: pair_cost(mode) for mode, label in PAIR_MODES.items()}
+    return {"single": single, "beside_mfma": beside, "block": blocks, "pair": pairs}
 
 
 def markdown(tab: dict) -> str:
-    out = ["| instruction | cycles at 2 waves/SIMD | 3 | 4 | clock GHz | 3 waves + a wave of matrix instructions: cycles | matrix instructions per 1000 cycles meanwhile (alone: 30.3) |",
-           "|---|---|---|---|---|---|---|"]
+    out = ["| instruction | cycles at 2 waves/SIMD | 3 | 4 | pace of the first wave to finish, 2 waves/SIMD | clock GHz | 3 waves + a wave of matrix instructions: cycles | matrix instructions per 1000 cycles meanwhile (alone: 30.3) |",
+           "|---|---|---|---|---|---|---|---|"]
     for name, row in tab["single"].items():
         b = tab["beside_mfma"].get(name)
-        out.append("| `%s` | %.2f | %.2f | %.2f | %.2f | %s | %s |" % (name, row[2][0], row[3][0], row[4][0], row[3][1],
-                                                                 "%.2f" % b[0] if b else "-", "%.1f" % b[2] if b else "-"))
+        out.append("| `%s` | %.2f | %.2f | %.2f | %.2f | %.2f | %s | %s |" % (name, row[2][0], row[3][0], row[4][0], row[2][3], row[3][1],
+                                                                        "%.2f" % b[0] if b else "-", "%.1f" % b[2] if b else "-"))
     out += ["", "| block replica (cycles per wave-block per SIMD) | 2 waves/SIMD | 3 | 4 | clock GHz |", "|---|---|---|---|---|"]
     for label, row in tab["block"].items():
         out.append("| %s | %.0f | %.0f | %.0f | %.2f |" % (label, row[2][0], row[3][0], row[4][0], row[3][1]))
+    out += ["", "| two-halves replica, 2 waves/SIMD (cycles per half-block per SIMD) | cycles | first wave to finish | clock GHz |", "|---|---|---|---|"]
+    for label, row in tab["pair"].items():
+        out.append("| %s | %.0f | %.0f | %.2f |" % (label, row[0], row[3], row[1]))
     return "\n".join(out)
 
 

@@ -40,3 +40,58 @@ def test_kernels_contain_no_inline_assembly_instructions():
             if m.group(1).strip():
                 found.append((os.path.basename(path), m.group(1)))
     assert found == [], found
+
+
+LISTING = """\t.text
+_ZN4paro11attn_i8_demoEv:                ; @_ZN4paro11attn_i8_demoEv
+; %bb.0:
+\tv_mov_b32_e32 v1, 0
+\ts_cbranch_scc1 .LBB0_3
+.LBB0_1:                                ; =>This Inner Loop Header: Depth=1
+\tv_mfma_i32_32x32x32_i8 v[0:15], v[16:19], v[20:23], v[0:15]
+\tv_fma_f32 v1, v2, v3, v4
+\tv_fmac_f32_e32 v1, v2, v3
+\tv_add_f32_e32 v1, v2, v3
+\tv_exp_f32_e32 v1, v1
+\tv_max3_i32 v1, v2, v3, v4
+\tv_permlane32_swap_b32_e32 v1, v2
+\tv_add_u32_e32 v1, v2, v3
+\ts_nop 1
+\tds_read_b128 v[4:7], v8
+\ts_cbranch_vccz .LBB0_1
+.LBB0_2:                                ; =>This Inner Loop Header: Depth=1
+\tv_add_f32_e32 v1, v2, v3
+\ts_cbranch_vccz .LBB0_2
+.LBB0_3:
+\ts_endpgm
+"""
+
+
+def test_loop_instruction_counts_reads_the_loops_that_hold_matrix_instructions():
+    """bench.py's issue-cost roofline multiplies these counts by measured per-class costs: the parser must count
+    vector instructions of loop blocks only, class them as the probe prices them, and skip loops without
+    matrix instructions."""
+    from paper_2506_16054_amd.build import instruction_class, loop_instruction_counts
+
+    got = loop_instruction_counts(LISTING)
+    assert got == {"_ZN4paro11attn_i8_demoEv": [{"mfma": 1, "fma": 2, "add_mul": 1, "transcendental": 1, "half_rate": 1,
+                                                 "permlane_swap": 1, "int_simple": 1}]}
+    assert instruction_class("v_cvt_pknorm_u16_f32") == "half_rate"
+    assert instruction_class("v_mul_f32_e32") == "add_mul"
+
+
+def test_probe_library_exports_what_bench_calls():
+    """lib/libparo_probe.so is a measurement aid next to the product library; bench.py fails if it is missing."""
+    import ctypes
+    import os
+
+    import torch  # noqa: F401  (before the library, as probe.lib() does: both must bind to the same HIP runtime)
+
+    from paper_2506_16054_amd.probe import LIBPATH
+
+    assert os.path.exists(LIBPATH), "build with python -m paper_2506_16054_amd.build"
+    lib = ctypes.CDLL(LIBPATH)
+    for name in ("paro_probe_mfma", "paro_probe_last_error", "paro_probe_issue_kinds", "paro_probe_issue_name", "paro_probe_issue",
+                 "paro_probe_block", "paro_probe_pair"):
+        assert hasattr(lib, name), name
+    assert lib.paro_probe_issue_kinds() >= 22
