@@ -33,6 +33,8 @@ def attention_kernel_symbol(w):
     if w.block == 64 and w.d == 64 and w.bits_qk == 8:
         return ("_ZN4paro18attn_i8_w64_kernelILi%dE%sEEvNS_8AttnArgsE" % (w.bits_pv, t),
                 "paro::attn_i8_w64_kernel<%d, %s>" % (w.bits_pv, tn), 1, 2)
+    if w.block == 64 and w.d == 128 and w.bits_qk == 8 and w.bits_pv == 8:
+        return ("_ZN4paro18attn_i8_q16_kernelI%sEEvNS_8AttnArgsE" % t, "paro::attn_i8_q16_kernel<%s>" % tn, 4, 4)
     return ("_ZN4paro14attn_i8_kernelILi%dELi%dELi%dELi%dE%sLi0EEEvNS_8AttnArgsE" % (w.block, w.d, w.bits_qk, w.bits_pv, t),
             "paro::attn_i8_kernel<%d, %d, %d, %d, %s, 0>" % (w.block, w.d, w.bits_qk, w.bits_pv, tn), w.block // 32, 3 if w.d == 64 else 2)
 
@@ -85,7 +87,8 @@ def recorded_counters(w, live_blocks):
 
 
 PROBE_OF_CLASS = {"fma": "v_fma_f32", "add_mul": "v_add_f32", "int_simple": "v_add_u32", "half_rate": "v_max3_i32",
-                  "transcendental": "v_exp_f32", "permlane_swap": "v_permlane32_swap_b32", "mfma": "v_mfma_i32_32x32x32_i8"}
+                  "transcendental": "v_exp_f32", "permlane_swap": "v_permlane32_swap_b32", "mfma": "v_mfma_i32_32x32x32_i8",
+                  "mfma_16x16": "v_mfma_i32_16x16x64_i8"}
 
 
 def valu_issue_roofline(w, live_blocks, attn_ms, n_cus):
@@ -108,7 +111,7 @@ def valu_issue_roofline(w, live_blocks, attn_ms, n_cus):
     iterations = live_blocks * waves
     simds = 4 * n_cus
     model_ms = sum(static[c] * cost_ns[c] for c in static) * iterations / simds * 1e-6
-    model_no_mfma_ms = sum(static[c] * cost_ns[c] for c in static if c != "mfma") * iterations / simds * 1e-6
+    model_no_mfma_ms = sum(static[c] * cost_ns[c] for c in static if not c.startswith("mfma")) * iterations / simds * 1e-6
     return {
         "bound": "valu_issue",
         "kernel": name,

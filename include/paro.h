@@ -225,8 +225,11 @@ int paro_sparse_attn_unpermuted(const paro_shape* s, int bits_qk, int bits_pv, c
 /* paro_sparse_attn_unpermuted with the reorder and quantization of Q folded in as well: the
  * quantization group of Q is the 64-token row block one workgroup owns (Sec. 4.3 (1): groups aligned
  * with the attention block), so each workgroup gathers its rows of Q by the head's axis order and
- * quantizes them to 8 bits itself; the Q codes and scales never exist in memory.  Results are
- * bit-identical to paro_permute_quantize(Q, bits 8) + paro_sparse_attn_unpermuted(bits_qk 8).
+ * quantizes them to 8 bits itself; the Q codes and scales never exist in memory.  Codes and scales are
+ * those of paro_permute_quantize(Q, bits 8), and the result is bit-identical to that call followed by
+ * paro_sparse_attn_unpermuted(bits_qk 8) - except at d = 128 with bits_pv 8, where the two entry points run
+ * different kernels whose floating-point sums associate differently: there the results agree to the
+ * rounding of the output type.
  *   q_dtype  type of q;  q  [B,nh,N,d], default token order, unquantized
  *   bits_pv  8 or 4;  k, sk, v, sv and everything else as in paro_sparse_attn_unpermuted (bits_qk 8)
  * Requires block == 64 (PARO_EUNSUPPORTED otherwise). */

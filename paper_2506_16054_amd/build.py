@@ -69,14 +69,14 @@ def _compile(src: str, extra, objdir: str = LIBDIR) -> str:
 
 
 # ---- static instruction counts of the attention kernels' block loops (read by bench.py) --------------------
-_RARE = 24  # a loop block with this many v_cndmask or v_mul is a rarely taken branch (ragged-tail masking, re-referencing)
+_RARE = 12  # a loop block with this many v_cndmask or v_mul is a rarely taken branch (ragged-tail masking, re-referencing)
 
 
 def instruction_class(op: str) -> str:
     """Issue class of a vector instruction mnemonic, as priced by the instruction-issue probe."""
     op = re.sub(r"_(e32|e64|dpp|sdwa)$", "", op)
     if "mfma" in op:
-        return "mfma"
+        return "mfma_16x16" if "_16x16x" in op else "mfma"
     if op in ("v_exp_f32", "v_rcp_f32", "v_log_f32", "v_rsq_f32", "v_sqrt_f32", "v_exp_f16"):
         return "transcendental"
     if op.startswith("v_permlane"):
@@ -122,7 +122,7 @@ def loop_instruction_counts(asm: str) -> dict:
                 for o in ops:
                     c = instruction_class(o)
                     counts[c] = counts.get(c, 0) + 1
-            if counts.get("mfma"):
+            if counts.get("mfma") or counts.get("mfma_16x16"):
                 entries.append(counts)
         if entries:
             out[name] = entries

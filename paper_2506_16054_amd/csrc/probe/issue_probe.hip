@@ -468,6 +468,14 @@ __global__ __launch_bounds__(256) void pair_kernel(int iters, WaveTimes* __restr
         l[h] = fmaf(rs, 0.5f, l[h]);                                                    \
         w[h] = 1.0f / (1.0f + l[h]);                                                    \
     }
+// the logit fma and the exp2 of a run of 8 as separate pieces (MODE 5: the exponentials directly behind a matrix
+// instruction, the next run's fma in front of the next matrix instruction)
+#define PAIR_SM_FMA(h, g)                                                               \
+    _Pragma("unroll") for (int r = 0; r < 8; ++r)                                       \
+        ev[(g) >> 1][8 * ((g) & 1) + r] = fmaf(__int_as_float(s[h][(g) >> 1][8 * ((g) & 1) + r]), c, off);
+#define PAIR_SM_EXPONLY(g)                                                              \
+    _Pragma("unroll") for (int r = 0; r < 8; ++r)                                       \
+        ev[(g) >> 1][8 * ((g) & 1) + r] = __builtin_amdgcn_exp2f(ev[(g) >> 1][8 * ((g) & 1) + r]);
 // matrix instruction first, then the piece's vector instructions
 #define PAIR_MFMA_FIRST()                                                               \
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  \
@@ -480,7 +488,24 @@ __global__ __launch_bounds__(256) void pair_kernel(int iters, WaveTimes* __restr
     const long long t0 = wall_clock64();
     if constexpr (MODE == 2) { PAIR_QK(0) PAIR_FENCE(); }
     for (int it = 0; it < iters; ++it) {
-        if constexpr (MODE == 3 || MODE == 4) {
+        if constexpr (MODE == 5) {
+            PAIR_QK(0) PAIR_FENCE();
+            PAIR_SM_HEAD(0) PAIR_SM_FMA(0, 0) PAIR_FENCE();
+            PAIR_QK1(1, 0) PAIR_FENCE(); PAIR_SM_EXPONLY(0) PAIR_SM_FMA(0, 1) PAIR_FENCE();
+            PAIR_QK1(1, 1) PAIR_FENCE(); PAIR_SM_EXPONLY(1) PAIR_SM_FMA(0, 2) PAIR_FENCE();
+            PAIR_QK1(1, 2) PAIR_FENCE(); PAIR_SM_EXPONLY(2) PAIR_SM_FMA(0, 3) PAIR_FENCE();
+            PAIR_QK1(1, 3) PAIR_FENCE(); PAIR_SM_EXPONLY(3) PAIR_FENCE();
+            PAIR_SM_TAIL(0) PAIR_FENCE();
+            PAIR_SM_HEAD(1) PAIR_SM_FMA(1, 0) PAIR_FENCE();
+            PAIR_PV1(0, 0) PAIR_FENCE(); PAIR_SM_EXPONLY(0) PAIR_SM_FMA(1, 1) PAIR_FENCE();
+            PAIR_PV1(0, 1) PAIR_FENCE(); PAIR_SM_EXPONLY(1) PAIR_SM_FMA(1, 2) PAIR_FENCE();
+            PAIR_PV1(0, 2) PAIR_FENCE(); PAIR_SM_EXPONLY(2) PAIR_SM_FMA(1, 3) PAIR_FENCE();
+            PAIR_PV1(0, 3) PAIR_FENCE(); PAIR_SM_EXPONLY(3) PAIR_FENCE();
+            PAIR_SM_TAIL(1) PAIR_FENCE();
+            PAIR_UPDATE(0) PAIR_FENCE();
+            PAIR_PV(1) PAIR_FENCE();
+            PAIR_UPDATE(1) PAIR_FENCE();
+        } else if constexpr (MODE == 3 || MODE == 4) {
             // MODE 4: the same pieces in the same order without the matrix instructions moved in (they run as two
             // groups of four in front of each softmax), as the reference for MODE 3
             PAIR_QK(0) PAIR_FENCE();
@@ -551,6 +576,8 @@ __global__ __launch_bounds__(256) void pair_kernel(int iters, WaveTimes* __restr
 #undef PAIR_SM_HEAD
 #undef PAIR_SM_EXP
 #undef PAIR_SM_TAIL
+#undef PAIR_SM_FMA
+#undef PAIR_SM_EXPONLY
 #undef PAIR_MFMA_FIRST
 #undef PAIR_PV
 #undef PAIR_SOFTMAX
@@ -659,10 +686,12 @@ int paro_probe_block(int parts, int cus, int waves_per_simd, int iters, int64_t*
 
 // Enqueues the two-halves replica (see pair_kernel) with two wavefronts per SIMD on `cus` compute units:
 // mode 0 program order, 1 matrix instructions of one half among the vector work of the other, 2 as 1 plus the
-// next visit's first products among the last update.  Every wavefront runs `iters` visits = 2 * iters half-blocks.
+// next visit's first products among the last update, 3 one matrix instruction in front of each run of 8 logit fma +
+// 8 exp2, 4 the pieces of 3 with the matrix instructions not moved in, 5 as 3 with the exp2 directly behind the
+// matrix instruction.  Every wavefront runs `iters` visits = 2 * iters half-blocks.
 // Output as paro_probe_issue.
 int paro_probe_pair(int mode, int cus, int iters, int64_t* times, int32_t* sink, int64_t capacity, void* stream) {
-    if (mode < 0 || mode > 4 || cus < 1 || cus > 4096 || iters < 1 || iters > (1 << 20) || !times || !sink) return kErrInval;
+    if (mode < 0 || mode > 5 || cus < 1 || cus > 4096 || iters < 1 || iters > (1 << 20) || !times || !sink) return kErrInval;
     const int entries = cus * 4 * 2;
     if (capacity < entries) return kErrInval;
     hipStream_t st = (hipStream_t)stream;
@@ -671,7 +700,8 @@ int paro_probe_pair(int mode, int cus, int iters, int64_t* times, int32_t* sink,
                    : mode == 1 ? launch_pair<1>(cus, iters, out, sink, st)
                    : mode == 2 ? launch_pair<2>(cus, iters, out, sink, st)
                    : mode == 3 ? launch_pair<3>(cus, iters, out, sink, st)
-                               : launch_pair<4>(cus, iters, out, sink, st);
+                   : mode == 4 ? launch_pair<4>(cus, iters, out, sink, st)
+                               : launch_pair<5>(cus, iters, out, sink, st);
     return rc < 0 ? rc : entries;
 }
 

@@ -123,6 +123,13 @@ constexpr int kAccBiasI = 0x4B400000;
 constexpr float kAccBiasF = 12582912.0f;
 __device__ inline float int_result(int raw) { return __int_as_float(raw) - kAccBiasF; }
 
+// The scale of a column block is the same for every lane and is written by the quantizer before this kernel
+// starts: read through the constant address space it becomes a scalar load, needs no vector register while it is
+// carried from one block to the next, and enters its one multiplication as a scalar operand.  Used by the kernel
+// with four wavefronts per row block (-1.4 % there); the one-wavefront kernel measures the same either way and
+// keeps its vector loads.
+__device__ inline float uniform_load(const float* p) { return *(const __attribute__((address_space(4))) float*)(unsigned long long)p; }
+
 // 1: with 8-bit P codes the accumulator bias of the logits is folded into the offset of the exponent's
 // fma (one vector instruction per logit less); 0: the bias is always subtracted first and the exponent is
 // exact to fp32 rounding.  With 4-bit P codes a code that flips at a rounding tie moves an output element
@@ -649,11 +656,15 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
     const float sq_i = a.sq[(size_t)bh * a.kblocks + i] * a.qk_scale;
     int row[2];
     bool row_valid[2];
+    unsigned invalid_row[2];
     v4i qf[2][2];  // [half][contraction step]
 #pragma unroll
     for (int H = 0; H < 2; ++H) {
         row[H] = i * BLK + 32 * H + n;
         row_valid[H] = row[H] < a.n_tokens;
+        // or-ed into the bit pattern of a value <= 0 it gives a pattern at or above that of -inf: larger, as an
+        // unsigned number, than the pattern of every value a real row can have
+        invalid_row[H] = row_valid[H] ? 0u : 0xFF800000u;
         const uint8_t* qrow = a.q + (head_rows + row[H]) * D + 16 * g;
 #pragma unroll
         for (int s = 0; s < 2; ++s) qf[H][s] = *(const v4i*)(qrow + 32 * s);
@@ -775,7 +786,7 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
                 for (int r = 0; r < 16; ++r) part[r & 3] = max(part[r & 3], sacc[H][T][r]);
             const float ymax = c * int_result(xor32_max(max(max(part[0], part[1]), max(part[2], part[3]))));
             m_new[H] = fmaxf(m[H], ymax);
-            if (row_valid[H]) eb = min(eb, __float_as_uint(ymax - m_new[H]));
+            eb = min(eb, __float_as_uint(ymax - m_new[H]) | invalid_row[H]);  // a padded row loses the minimum
         }
         const float e = __uint_as_float(wave_umin(eb));
         if (__builtin_amdgcn_ballot_w64(m_new[0] - m_ref[0] > 64.0f || m_new[1] - m_ref[1] > 64.0f) != 0) {
@@ -893,6 +904,295 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
                     store4(orow + 32 * dt + 8 * qd, acc[H][dt][4 * qd] * inv, acc[H][dt][4 * qd + 1] * inv, acc[H][dt][4 * qd + 2] * inv,
                            acc[H][dt][4 * qd + 3] * inv);
         }
+    }
+}
+
+// -------------------------------------------------------------------------------------------
+// d = 128, block 64, 8-bit Q, K, P and V codes: FOUR wavefronts per row block, 16 queries each, on
+// v_mfma_i32_16x16x64_i8.
+//
+// At d = 128 a wavefront of 32 queries carries 64 accumulator registers and needs ~200 in all: two
+// wavefronts per SIMD, each alone for long stretches, and a row block that attends every column block (the
+// text rows of an image model, Sec. 4.2 (1)) is a chain of 72 such block visits that the whole launch
+// waits for.  With 16 queries per wavefront the visit is half as long, the registers allow three
+// wavefronts per SIMD, and the matrix work is unchanged (a 16x16x64 instruction takes half the time of a
+// 32x32x32 one).
+//
+// Layouts.  S^T tile T (16 keys x 16 queries): lane (n = lane % 16, G = lane / 16) holds query n, keys
+// 4 G + r (r = 0..3) of the tile.  Which key sits in which row of a tile is free - K rows are fetched from
+// LDS by address - and is chosen so that the four codes of a lane's tile T land, packed into register T
+// of the B operand, on the contraction slots 16 G + 4 T + r that lane group G of the PV instruction
+// covers: row 4 G + r of tile T is the key whose PARO_VT slot is 16 G + 4 T + r, i.e. token
+// 32 (G >> 1) + 8 T + 4 (G & 1) + r of the block.  V^T fragments are then plain 16-byte reads of PARO_VT rows.
+//
+// Tiles.  K_j (64 x 128 B) and V_j^T (128 x 64 B) are contiguous 8 KB in global memory and go to LDS as
+// they are with global_load_lds_dwordx4, each wavefront moving a quarter, except that inside every 128-byte
+// line the eight 16-byte pieces are stored at position (piece ^ line % 8): the reads of 16 lanes that walk
+// down a column of pieces then spread over all banks.  Two K slots and two V slots; ONE barrier per block,
+// after the wavefront has written its share of the tile exponent and waited for its own requests: behind
+// it K_{t+2} may overwrite K_t (all K_t reads precede the barrier) and V_{t+1} may overwrite V_{t-1}.
+// Arithmetic per block as in attn_i8_kernel.
+// -------------------------------------------------------------------------------------------
+#ifndef PARO_ATTN_Q16
+#define PARO_ATTN_Q16 1
+#endif
+
+typedef int v4acc __attribute__((ext_vector_type(4)));
+
+// max over the four lanes n, n + 16, n + 32, n + 48 (the lanes that share a query), returned in all four
+__device__ inline int quad_rows_max(int x) {
+    const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+    return xor32_max(max((int)r[0], (int)r[1]));
+}
+__device__ inline float quad_rows_sum(float x) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_int(x), __float_as_int(x), false, false);
+    const float y = __int_as_float((int)r[0]) + __int_as_float((int)r[1]);
+    return y + __shfl_xor(y, 32);
+}
+
+template <typename OutT>
+__global__ __launch_bounds__(256, 3) void attn_i8_q16_kernel(AttnArgs a) {
+    constexpr int BLK = 64, D = 128;
+    constexpr int KS = D / 64;     // contraction steps of QK^T (64 channels each)
+    constexpr int CT = D / 16;     // 16-channel tiles of the output
+    constexpr int TILE = BLK * D;  // bytes of a K tile and of a V^T tile
+    constexpr float LOG2_QMAXP = 6.988684686772166f;
+    constexpr float kLog2_65535 = 15.999977986052736f;
+    __shared__ __attribute__((aligned(16))) uint8_t kring[2][TILE];
+    __shared__ __attribute__((aligned(16))) uint8_t vring[2][TILE];
+    __shared__ unsigned tile_e[2][4];
+
+    const int wg = blockIdx.x;
+    const int logical = (wg & 7) * a.per_xcd + (wg >> 3);
+    if (logical >= a.total_wg) return;
+    const int item = a.row_order ? min(max(a.row_order[logical], 0), a.total_wg - 1) : logical;
+    const int bh = item / a.kblocks;
+    const int i = item - bh * a.kblocks;
+    const int h = bh % a.nh;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15;
+    const int G = lane >> 4;
+
+    const int* rp = a.row_ptr + (size_t)h * (a.kblocks + 1) + i;
+    const int beg = __builtin_amdgcn_readfirstlane(min(max(rp[0], 0), a.nnz));
+    const int end = __builtin_amdgcn_readfirstlane(min(max(rp[1], beg), a.nnz));
+    const int cnt = end - beg;
+    const int* cols = a.col_idx + beg;
+    if (2 * cnt > a.kblocks) __builtin_amdgcn_s_setprio(2);
+
+    const size_t head_rows = (size_t)bh * a.kblocks * BLK;
+    const uint8_t* kbase = a.k + head_rows * D;
+    const uint8_t* vbase = a.v + head_rows * D;
+    const float* skp = a.sk + (size_t)bh * a.kblocks;
+    const float* svp = a.sv + (size_t)bh * a.kblocks;
+    const float sq_i = a.sq[(size_t)bh * a.kblocks + i] * a.qk_scale;
+    const int row = i * BLK + 16 * w + n;  // this lane's query, in the reordered sequence
+    const bool row_valid = row < a.n_tokens;
+    // or-ed into the bit pattern of a value <= 0 it gives a pattern at or above that of -inf: larger, as an unsigned
+    // number, than the pattern of every value a real row can have
+    const unsigned invalid_row = row_valid ? 0u : 0xFF800000u;
+    v4i qf[KS];
+    {
+        const uint8_t* qrow = a.q + (head_rows + row) * D + 16 * G;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qf[s] = *(const v4i*)(qrow + 64 * s);
+    }
+    // a wavefront moves two of the eight 1 KB pieces of a tile: lane L fills LDS bytes 16 L of the piece, which is
+    // position L % 8 of line L / 8 and holds the line's global piece (L % 8) ^ (L / 8)
+    const unsigned fill_lane = 2048u * w + 128u * (lane >> 3) + 16u * ((lane & 7) ^ (lane >> 3));
+    // K fragment of tile T, step s: row 32 (n >> 3) + 8 T + (n & 7) of the tile, piece 4 s + G
+    unsigned kread[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) kread[s] = 128u * (32 * (n >> 3) + (n & 7)) + 16u * ((4 * s + G) ^ (n & 7));
+    // V^T fragment of channel tile ct: PARO_VT row 16 ct + n = line 8 ct + n / 2, piece 4 (n % 2) + G
+    const unsigned vread = 128u * (n >> 1) + 16u * ((4 * (n & 1) + G) ^ (n >> 1));
+
+    // column indices: 64 per fetch, one per lane; `cols_cur` holds the chunk of the newest step looked up
+    auto load_cols = [&](int chunk) {
+        const int idx = min(chunk * 64 + lane, cnt - 1);
+        return cnt > 0 && chunk * 64 < cnt ? min(max(cols[idx], 0), a.kblocks - 1) : 0;
+    };
+    int cols_cur = load_cols(0), cols_nxt = load_cols(1);
+    int cur_chunk = 0;
+    auto col_at = [&](int u) {  // u advances by one per call
+        if ((u & 63) == 0 && u > 0) {
+            cols_cur = cols_nxt;
+            ++cur_chunk;
+            cols_nxt = load_cols(cur_chunk + 1);
+        }
+        return __builtin_amdgcn_readlane(cols_cur, u & 63);
+    };
+    auto request_k = [&](int j, int slot) {
+        const uint8_t* kp = kbase + (size_t)j * TILE;
+        lds_dma16<0>(kp, fill_lane, &kring[slot][2048 * w]);
+        lds_dma16<1024>(kp, fill_lane, &kring[slot][2048 * w + 1024]);
+    };
+    auto request_v = [&](int j, int slot) {
+        const uint8_t* vp = vbase + (size_t)j * TILE;
+        lds_dma16<0>(vp, fill_lane, &vring[slot][2048 * w]);
+        lds_dma16<1024>(vp, fill_lane, &vring[slot][2048 * w + 1024]);
+    };
+
+    float m = -INFINITY, m_ref = -INFINITY, w_base = INFINITY, l = 0.0f;
+    float acc[CT][4];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[ct][r] = 0.0f;
+    v4acc acc_init = {kAccBiasI, kAccBiasI, kAccBiasI, kAccBiasI};
+    asm volatile("" : "+v"(acc_init));
+
+    // columns of the steps t, t + 1, t + 2 and the scales of t, t + 1
+    int j0 = 0, j1 = 0, j2 = 0;
+    float sk0 = 0.0f, sv0 = 0.0f, sk1 = 0.0f, sv1 = 0.0f;
+    if (cnt > 0) {
+        j0 = col_at(0);
+        request_k(j0, 0);
+        request_v(j0, 0);
+        sk0 = uniform_load(skp + j0);
+        sv0 = uniform_load(svp + j0);
+        if (cnt > 1) {
+            j1 = col_at(1);
+            request_k(j1, 1);
+            sk1 = uniform_load(skp + j1);
+            sv1 = uniform_load(svp + j1);
+        }
+        if (cnt > 2) j2 = col_at(2);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    __syncthreads();
+    const int tail_block = (a.n_tokens % BLK) != 0 ? a.kblocks - 1 : -1;  // the column block with padded keys, if any
+
+    auto step = [&](auto fold_tag, int t) {
+        constexpr bool FOLD = decltype(fold_tag)::value;
+        const float c = sq_i * sk0;
+        const float sv_now = sv0;
+        const uint8_t* kslot = &kring[t & 1][0];
+        const uint8_t* vslot = &vring[t & 1][0];
+
+        // ---- S^T = K_j Q_i^T (i32, biased): four 16-key tiles
+        v4acc sacc[4];
+#pragma unroll
+        for (int T = 0; T < 4; ++T) {
+            sacc[T] = acc_init;
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                sacc[T] = __builtin_amdgcn_mfma_i32_16x16x64_i8(*(const v4i*)(kslot + 1024 * T + kread[s]), qf[s], sacc[T], 0, 0, 0);
+        }
+        if (j0 == tail_block) {  // keys past N: the bit pattern of -inf loses every maximum and gives E = 0
+            const int nkeys = a.n_tokens - (a.kblocks - 1) * BLK;
+#pragma unroll
+            for (int T = 0; T < 4; ++T)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (32 * (G >> 1) + 8 * T + 4 * (G & 1) + r >= nkeys) sacc[T][r] = (int)0xFF800000;
+        }
+        // ---- running maximum and this wavefront's share of the tile's quantization scale
+        int part[4] = {0, 0, 0, 0};  // below every real value (those carry the accumulator bias)
+#pragma unroll
+        for (int T = 0; T < 4; ++T)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part[r] = max(part[r], sacc[T][r]);
+        const float ymax = c * int_result(quad_rows_max(max(max(part[0], part[1]), max(part[2], part[3]))));
+        const float m_new = fmaxf(m, ymax);
+        unsigned eb = __float_as_uint(ymax - m_new) | invalid_row;  // a padded row loses the minimum
+        eb = min(eb, (unsigned)dpp_mov<0xB1>((int)eb));  // the four rows of 16 lanes hold the same 16 queries:
+        eb = min(eb, (unsigned)dpp_mov<0x4E>((int)eb));  // one row is reduced
+        eb = min(eb, (unsigned)dpp_mov<0x141>((int)eb));
+        eb = min(eb, (unsigned)dpp_mov<0x140>((int)eb));
+        if (lane == 0) tile_e[t & 1][w] = eb;
+        // ---- everything this wavefront has in flight (its share of K_{t+1} and V_t) has landed; behind the
+        // barrier both tiles and all four exponents are whole, K_t has been read by all and V_{t-1} is consumed
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (t + 1 < cnt) request_v(j1, (t + 1) & 1);
+        if (t + 2 < cnt) request_k(j2, t & 1);
+        const float e = __uint_as_float(min(min(tile_e[t & 1][0], tile_e[t & 1][1]), min(tile_e[t & 1][2], tile_e[t & 1][3])));
+        // the next step's column, scales and the column after it (scalar work, hidden behind the vector work below)
+        j0 = j1;
+        j1 = j2;
+        sk0 = sk1;
+        sv0 = sv1;
+        if (t + 2 < cnt) {
+            sk1 = uniform_load(skp + j1);
+            sv1 = uniform_load(svp + j1);
+        }
+        if (t + 3 < cnt) j2 = col_at(t + 3);
+
+        if (__builtin_amdgcn_ballot_w64(m_new - m_ref > 64.0f) != 0) {
+            const float down = __builtin_amdgcn_exp2f(m_ref - m_new);  // first block: 2^-inf = 0 on zero sums
+            l *= down;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[ct][r] *= down;
+            m_ref = m_new;
+            w_base = -kLog2_65535 - m_new;
+        }
+        m = m_new;
+        const float off_n = (LOG2_QMAXP - kLog2_65535) - m_new - e;
+        float off_f = off_n, w_blk;
+        if constexpr (FOLD) {
+            const float cb_hi = c * kAccBiasF;
+            const float cb_lo = fmaf(c, kAccBiasF, -cb_hi);
+            off_f = off_n - cb_hi;
+            const float bb = off_f - off_n;
+            const float terr = (off_n - (off_f - bb)) + (-cb_hi - bb);
+            w_blk = __builtin_amdgcn_exp2f((w_base - off_n) - (cb_lo - terr));
+        } else {
+            w_blk = __builtin_amdgcn_exp2f(w_base - off_n);
+        }
+        // ---- E (in place of the raw logits), row sum, codes packed as B operand: register T = tile T
+        float ev[4][4];
+#pragma unroll
+        for (int T = 0; T < 4; ++T)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                ev[T][r] = __builtin_amdgcn_exp2f(fmaf(FOLD ? __int_as_float(sacc[T][r]) : int_result(sacc[T][r]), c, off_f));
+        const float rs = ((ev[0][0] + ev[0][1]) + (ev[0][2] + ev[0][3])) + ((ev[1][0] + ev[1][1]) + (ev[1][2] + ev[1][3])) +
+                         (((ev[2][0] + ev[2][1]) + (ev[2][2] + ev[2][3])) + ((ev[3][0] + ev[3][1]) + (ev[3][2] + ev[3][3])));
+        v4i pf;
+#pragma unroll
+        for (int T = 0; T < 4; ++T) {
+            const unsigned lo = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[T][0], ev[T][1]));
+            const unsigned hi = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pknorm_u16(ev[T][2], ev[T][3]));
+            pf[T] = (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u);
+        }
+        l = fmaf(rs, w_blk, l);
+        // ---- O^T += (sP sv_j 2^(m' - m_ref)) V_j^T P^T: eight 16-channel tiles, one instruction each
+        const float sv_eff = w_blk * sv_now;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            const v4acc o = __builtin_amdgcn_mfma_i32_16x16x64_i8(*(const v4i*)(vslot + 1024 * ct + vread), pf, acc_init, 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[ct][r] = fmaf(int_result(o[r]), sv_eff, acc[ct][r]);
+        }
+    };
+
+    constexpr bool FOLDABLE = PARO_FOLD_LOGIT_BIAS;
+    bool fold = false;
+    if constexpr (FOLDABLE) {  // same rule as attn_i8_kernel
+        float sk_max = 0.0f;
+        for (int base = 0; base < cnt; base += 64)
+            if (base + lane < cnt) sk_max = fmaxf(sk_max, skp[min(max(cols[base + lane], 0), a.kblocks - 1)]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) sk_max = fmaxf(sk_max, __shfl_xor(sk_max, off));
+        fold = sq_i * sk_max * kAccBiasF < 8192.0f;
+    }
+    if (fold) {
+        for (int t = 0; t < cnt; ++t) step(std::bool_constant<FOLDABLE>{}, t);
+    } else {
+        for (int t = 0; t < cnt; ++t) step(std::false_type{}, t);
+    }
+
+    const float l_tot = quad_rows_sum(l) * 65535.0f;
+    const float inv = (row_valid && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
+    const long long ooff = out_row_offset<D>(a, bh, h, head_rows, row, row_valid);
+    if (ooff >= 0) {
+        OutT* orow = (OutT*)a.op + ooff + 4 * G;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) store4(orow + 16 * ct, acc[ct][0] * inv, acc[ct][1] * inv, acc[ct][2] * inv, acc[ct][3] * inv);
     }
 }
 
@@ -1184,6 +1484,14 @@ static void launch_i8(int blk, int d, paro_dtype out_dtype, const AttnArgs& a, h
             dim3 grid((unsigned)(a.per_xcd * 8));
             if (out_dtype == PARO_F32) hipLaunchKernelGGL((attn_i8_w64_kernel<PVBITS, float>), grid, dim3(64), 0, st, a);
             else hipLaunchKernelGGL((attn_i8_w64_kernel<PVBITS, uint16_t>), grid, dim3(64), 0, st, a);
+            return;
+        }
+    }
+    if constexpr (PARO_ATTN_Q16 && QKBITS == 8 && PVBITS == 8) {
+        if (blk == 64 && d == 128) {  // four wavefronts of 16 queries per row block
+            dim3 grid((unsigned)(a.per_xcd * 8));
+            if (out_dtype == PARO_F32) hipLaunchKernelGGL((attn_i8_q16_kernel<float>), grid, dim3(256), 0, st, a);
+            else hipLaunchKernelGGL((attn_i8_q16_kernel<uint16_t>), grid, dim3(256), 0, st, a);
             return;
         }
     }

@@ -150,6 +150,7 @@ PAIR_MODES = {
     2: "as 1, and QK(0) of the next visit among update(1)",
     3: "one matrix instruction in front of every 8 x (logit fma, exp2): QK(1) in softmax(0), PV(0) in softmax(1)",
     4: "the pieces of 3 in the same order, matrix instructions not moved in",
+    5: "as 3, skewed: each matrix instruction directly followed by 8 exp2, the next run's 8 logit fma behind them",
 }
 
 
