@@ -222,6 +222,23 @@ int paro_sparse_attn_unpermuted(const paro_shape* s, int bits_qk, int bits_pv, c
                                 int64_t nnz, const int32_t* row_order, const uint8_t* h_perm_ids,
                                 paro_dtype out_dtype, void* o, void* stream);
 
+/* ---- optional pre-conditioning of K (not part of the paper's method; the paper's kernel derives from an
+ * 8-bit attention kernel that has it) --------------------------------------------------------------
+ * Subtracting one constant per (head, channel) from every key changes each logit of a query by the same
+ * amount, so the softmax - with or without the block mask - does not see it, while the quantizer of
+ * Sec. 4.3 (1) sees blocks without their common offset.
+ *
+ * paro_k_channel_mean: k_mean[b][h][c] = the mean of k[b][h][:, c] over the N tokens, accumulated in binary64
+ * and rounded to bfloat16 (stored as float).  Any constant is valid; the coarse rounding makes this one
+ * independent of the order of the additions, hence reproducible bit for bit.
+ *   k       [B,nh,N,d] of dtype (device), default token order;  k_mean  float32 [B,nh,d] (device)
+ * paro_permute_quantize_smoothed: paro_permute_quantize(layout PARO_ROWS) of k - k_mean, the subtraction
+ * (one binary32 operation per element, real tokens only: padded rows stay zero) fused into the loads.
+ *   bits 8 or 4;  codes, scales as in paro_quantize(PARO_ROWS). */
+int paro_k_channel_mean(const paro_shape* s, paro_dtype dtype, const void* k, float* k_mean, void* stream);
+int paro_permute_quantize_smoothed(const paro_shape* s, paro_dtype dtype, int bits, const uint8_t* h_perm_ids,
+                                   const void* k, const float* k_mean, void* codes, float* scales, void* stream);
+
 /* paro_sparse_attn_unpermuted with the reorder and quantization of Q folded in as well: the
  * quantization group of Q is the 64-token row block one workgroup owns (Sec. 4.3 (1): groups aligned
  * with the attention block), so each workgroup gathers its rows of Q by the head's axis order and

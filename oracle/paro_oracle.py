@@ -269,6 +269,21 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
     return u.view(np.float32).astype(np.float64)
 
 
+def k_channel_mean(k: np.ndarray) -> np.ndarray:
+    """Optional pre-conditioning of K (not part of the paper's method; 8-bit attention kernels of the family its
+    kernel derives from have it): the constant removed from channel c of every key of a head is the mean of
+    k[:, c] over the N tokens, taken in float64 and rounded to bfloat16.  Returned as float32 [d]."""
+    mean64 = np.asarray(k, dtype=np.float64).mean(axis=0)
+    return round_to_bf16(mean64.astype(np.float32)).astype(np.float32)
+
+
+def smooth_k(k: np.ndarray) -> np.ndarray:
+    """k - k_channel_mean(k), one binary32 subtraction per element (the quantizer that follows evaluates in
+    binary32 too).  A constant per channel shifts every logit of a query by the same amount, q . mean, which the
+    softmax over any set of keys does not see; only the quantization error of K changes."""
+    return (np.asarray(k, dtype=np.float32) - k_channel_mean(k)[None, :]).astype(np.float32)
+
+
 def prepare_operand(x: np.ndarray, idx: np.ndarray, npad: int, block: int, bits: int):
     """permute + quantize one of Q/K/V of one head.
     bits 8 / 4: integer codes and per-block scales; bits 16: the unquantized mode, operands held
@@ -293,10 +308,14 @@ def paro_attention_head(
     col_idx: np.ndarray,
     bits_qk: int,
     bits_pv: int,
+    smooth: bool = False,
 ) -> np.ndarray:
     """permute -> quantize -> block-sparse attention -> inverse permute for one head.
-    q, k, v: [N, d] in the default token order.  Returns O float64 [N, d]."""
+    q, k, v: [N, d] in the default token order.  smooth: K is replaced by smooth_k(K) first.
+    Returns O float64 [N, d]."""
     F, Hg, Wg = grid
+    if smooth:
+        k = smooth_k(k)
     n = q.shape[0]
     kblocks = -(-n // block)
     npad = kblocks * block

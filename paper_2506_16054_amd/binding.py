@@ -30,6 +30,7 @@ EXPORTS = (
     "paro_quantize", "paro_sparse_attn", "paro_permute_quantize", "paro_sparse_attn_unpermuted", "paro_schedule_rows", "paro_check_blocklist", "paro_check_row_order",
     "paro_mask_to_blocklist_device", "paro_calib_block_stats", "paro_calib_metrics", "paro_calib_choose", "paro_calib_mask",
     "paro_sparse_attn_unpermuted_rawq", "paro_blocklist_cols_device", "paro_permute_quantize_qkv",
+    "paro_k_channel_mean", "paro_permute_quantize_smoothed",
 )
 
 
@@ -83,6 +84,8 @@ def lib() -> ctypes.CDLL:
         L.paro_sparse_attn_unpermuted_rawq.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i32, vp, vp]
         L.paro_blocklist_cols_device.argtypes = [i32, i32, vp, vp, vp, i64, vp]
         L.paro_permute_quantize_qkv.argtypes = [sp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.paro_k_channel_mean.argtypes = [sp, i32, vp, vp, vp]
+        L.paro_permute_quantize_smoothed.argtypes = [sp, i32, i32, vp, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -285,6 +288,26 @@ def paro_permute_quantize_qkv(s: paro_shape, bits_qk: int, bits_pv: int, perm_id
     p = _perm_bytes(s, perm_ids)
     _check(lib().paro_permute_quantize_qkv(ctypes.byref(s), _dtype_code(q), int(bits_qk), int(bits_pv), p.ctypes.data, _ptr(q), _ptr(k),
                                            _ptr(v), _ptr(q_codes), _ptr(sq), _ptr(k_codes), _ptr(sk), _ptr(v_codes), _ptr(sv), _stream()))
+
+
+def paro_k_channel_mean(s: paro_shape, k, k_mean) -> None:
+    import torch
+
+    _require(k, "k", (s.B, s.nh, paro_ntokens(s), s.d))
+    _require(k_mean, "k_mean", (s.B, s.nh, s.d), torch.float32)
+    _check(lib().paro_k_channel_mean(ctypes.byref(s), _dtype_code(k), _ptr(k), _ptr(k_mean), _stream()))
+
+
+def paro_permute_quantize_smoothed(s: paro_shape, bits: int, perm_ids, k, k_mean, codes, scales) -> None:
+    import torch
+
+    _require(k, "k", (s.B, s.nh, paro_ntokens(s), s.d))
+    _require(k_mean, "k_mean", (s.B, s.nh, s.d), torch.float32)
+    _require(codes, "codes", codes_shape(s, bits, PARO_ROWS), torch.int8)
+    _require(scales, "scales", (s.B, s.nh, paro_nblocks(s)), torch.float32)
+    p = _perm_bytes(s, perm_ids)
+    _check(lib().paro_permute_quantize_smoothed(ctypes.byref(s), _dtype_code(k), int(bits), p.ctypes.data, _ptr(k), _ptr(k_mean),
+                                                _ptr(codes), _ptr(scales), _stream()))
 
 
 def paro_mask_to_blocklist_device(nh: int, k: int, bitmask, row_ptr, col_idx, nnz_out=None) -> None:

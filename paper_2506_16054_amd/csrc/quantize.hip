@@ -51,9 +51,12 @@ __device__ inline float wave_max(float v) {
 // GATHER = true : the input is x [bh][N][D] in the default token order and the reorder of
 //                 Sec. 4.1 happens on the way in (row n' of the group reads row idx(n') of x), so
 //                 the reordered tensor never exists in memory.
-template <typename InT, int BLK, int D, int BITS, int LAYOUT, bool GATHER>
+// SMOOTH: the per-(head, channel) constant sub[bh][c] is subtracted from every real token before anything else
+//         (padded rows stay zero): the smoothed tensor never exists in memory either.
+template <typename InT, int BLK, int D, int BITS, int LAYOUT, bool GATHER, bool SMOOTH = false>
 __device__ __forceinline__ void quantize_group(const InT* __restrict__ xp, uint8_t* __restrict__ codes, float* __restrict__ scales,
-                                               int n_tokens, int kblocks, const ReorderTable& table, int nh, int blk, int bh) {
+                                               int n_tokens, int kblocks, const ReorderTable& table, int nh, int blk, int bh,
+                                               const float* __restrict__ sub = nullptr) {
     constexpr int ELEMS = BLK * D;
     constexpr int CHUNKS = ELEMS / 8;  // 8 consecutive channels of one token per chunk
     constexpr int IT = (CHUNKS + 255) / 256;
@@ -92,6 +95,12 @@ __device__ __forceinline__ void quantize_group(const InT* __restrict__ xp, uint8
                 load8<InT>(tile + (size_t)src_row[row] * D + (chunk * 8) % D, x[it]);
             } else {
                 load8<InT>(tile + (size_t)chunk * 8, x[it]);
+            }
+            if constexpr (SMOOTH) {
+                float mu[8];
+                load8<float>(sub + (size_t)bh * D + (chunk * 8) % D, mu);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[it][e] -= mu[e];  // one binary32 subtraction per element
             }
         } else {
 #pragma unroll
@@ -185,6 +194,65 @@ __global__ __launch_bounds__(256) void quantize_kernel(const InT* __restrict__ x
                                                        float* __restrict__ scales, int n_tokens, int kblocks,
                                                        ReorderTable table, int nh) {
     quantize_group<InT, BLK, D, BITS, LAYOUT, GATHER>(xp, codes, scales, n_tokens, kblocks, table, nh, blockIdx.x, blockIdx.y);
+}
+
+// K with a per-channel constant removed (see paro_k_channel_mean): rows, reorder fused into the loads.
+template <typename InT, int BLK, int D, int BITS>
+__global__ __launch_bounds__(256) void quantize_smoothed_kernel(const InT* __restrict__ x, const float* __restrict__ sub,
+                                                                uint8_t* __restrict__ codes, float* __restrict__ scales, int n_tokens,
+                                                                int kblocks, ReorderTable table, int nh) {
+    quantize_group<InT, BLK, D, BITS, PARO_ROWS, true, true>(x, codes, scales, n_tokens, kblocks, table, nh, blockIdx.x, blockIdx.y, sub);
+}
+
+// Mean over the N tokens of every channel of every (batch, head), accumulated in binary64 and rounded to
+// bfloat16 (returned as float).  One workgroup of 1024 threads per (batch, head): a thread owns 8 channels of
+// every (1024 / (D/8))-th token; partial sums meet across the row lanes of a wavefront by shuffles and across
+// the 16 wavefronts through LDS.  Any constant would do for the smoothing (the softmax does not see it); the
+// coarse rounding makes this one independent of the order of the additions.
+template <typename InT, int D>
+__global__ __launch_bounds__(1024) void channel_mean_kernel(const InT* __restrict__ x, float* __restrict__ mean, int n_tokens) {
+    constexpr int CHUNKS = D / 8;          // 8-channel chunks per token
+    constexpr int ROWS = 1024 / CHUNKS;    // tokens per pass of the workgroup
+    __shared__ double part[16][D];
+    const int tid = threadIdx.x;
+    const int cc = tid % CHUNKS;
+    const int rl = tid / CHUNKS;
+    const InT* base = x + (size_t)blockIdx.x * n_tokens * D + cc * 8;
+    double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int r0 = rl; r0 < n_tokens; r0 += 4 * ROWS) {
+        float v[4][8];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int r = r0 + u * ROWS;
+            if (r < n_tokens) {
+                load8<InT>(base + (size_t)r * D, v[u]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[u][e] = 0.0f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += (double)v[u][e];
+    }
+    // lanes of a wavefront that own the same chunk are CHUNKS apart
+#pragma unroll
+    for (int off = CHUNKS; off < 64; off <<= 1)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += __shfl_xor(acc[e], off);
+    if ((tid & 63) < CHUNKS) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part[tid >> 6][cc * 8 + e] = acc[e];
+    }
+    __syncthreads();
+    if (tid < D) {
+        double sum = 0.0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) sum += part[w][tid];
+        const float m = (float)(sum / (double)n_tokens);
+        mean[(size_t)blockIdx.x * D + tid] = __uint_as_float(f32_to_bf16_bits(m) << 16);
+    }
 }
 
 // Q, K and V of one attention call in a single launch (blockIdx.z selects the tensor): Q and K as
@@ -346,4 +414,64 @@ extern "C" int paro_permute_quantize(const paro_shape* s, paro_dtype dtype, int 
                                      const uint8_t* h_perm_ids, const void* x, void* codes, float* scales, void* stream) {
     if (!h_perm_ids) return paro::fail(PARO_EINVAL, "perm_ids is NULL");
     return paro::quantize_entry("paro_permute_quantize", s, dtype, bits, layout, h_perm_ids, x, codes, scales, stream);
+}
+
+
+namespace paro {
+template <typename InT, int BLK, int D>
+static void launch_smoothed(int bits, dim3 grid, hipStream_t st, const void* x, const float* sub, void* codes, float* scales, int n, int k,
+                            const ReorderTable& t, int nh) {
+    if (bits == 8)
+        hipLaunchKernelGGL((quantize_smoothed_kernel<InT, BLK, D, 8>), grid, dim3(256), 0, st, (const InT*)x, sub, (uint8_t*)codes, scales, n, k, t, nh);
+    else
+        hipLaunchKernelGGL((quantize_smoothed_kernel<InT, BLK, D, 4>), grid, dim3(256), 0, st, (const InT*)x, sub, (uint8_t*)codes, scales, n, k, t, nh);
+}
+template <typename InT>
+static void launch_smoothed_shape(int blk, int d, int bits, dim3 grid, hipStream_t st, const void* x, const float* sub, void* codes,
+                                  float* scales, int n, int k, const ReorderTable& t, int nh) {
+    if (blk == 64 && d == 64) launch_smoothed<InT, 64, 64>(bits, grid, st, x, sub, codes, scales, n, k, t, nh);
+    else if (blk == 64 && d == 128) launch_smoothed<InT, 64, 128>(bits, grid, st, x, sub, codes, scales, n, k, t, nh);
+    else if (blk == 32 && d == 64) launch_smoothed<InT, 32, 64>(bits, grid, st, x, sub, codes, scales, n, k, t, nh);
+    else launch_smoothed<InT, 32, 128>(bits, grid, st, x, sub, codes, scales, n, k, t, nh);
+}
+}  // namespace paro
+
+extern "C" int paro_k_channel_mean(const paro_shape* s, paro_dtype dtype, const void* k, float* k_mean, void* stream) {
+    using namespace paro;
+    int64_t n, kb;
+    if (int st = check_shape(s, &n, &kb)) return st;
+    if (dtype != PARO_F32 && dtype != PARO_BF16) return fail(PARO_EINVAL, "dtype=%d is not a paro_dtype", (int)dtype);
+    if (!k || !k_mean) return fail(PARO_EINVAL, "k and k_mean must not be NULL");
+    if (((uintptr_t)k | (uintptr_t)k_mean) & 15) return fail(PARO_EINVAL, "k and k_mean must be 16-byte aligned");
+    const dim3 grid((unsigned)(s->B * s->nh));
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == PARO_F32) {
+        if (s->d == 64) hipLaunchKernelGGL((channel_mean_kernel<float, 64>), grid, dim3(1024), 0, st, (const float*)k, k_mean, (int)n);
+        else hipLaunchKernelGGL((channel_mean_kernel<float, 128>), grid, dim3(1024), 0, st, (const float*)k, k_mean, (int)n);
+    } else {
+        if (s->d == 64) hipLaunchKernelGGL((channel_mean_kernel<uint16_t, 64>), grid, dim3(1024), 0, st, (const uint16_t*)k, k_mean, (int)n);
+        else hipLaunchKernelGGL((channel_mean_kernel<uint16_t, 128>), grid, dim3(1024), 0, st, (const uint16_t*)k, k_mean, (int)n);
+    }
+    return check_launch("paro_k_channel_mean");
+}
+
+extern "C" int paro_permute_quantize_smoothed(const paro_shape* s, paro_dtype dtype, int bits, const uint8_t* h_perm_ids, const void* k,
+                                              const float* k_mean, void* codes, float* scales, void* stream) {
+    using namespace paro;
+    int64_t n, kb;
+    if (int st = check_shape(s, &n, &kb)) return st;
+    if (dtype != PARO_F32 && dtype != PARO_BF16) return fail(PARO_EINVAL, "dtype=%d is not a paro_dtype", (int)dtype);
+    if (bits != 8 && bits != 4) return fail(PARO_EINVAL, "bits=%d: expected 8 or 4", bits);
+    if (!h_perm_ids) return fail(PARO_EINVAL, "perm_ids is NULL");
+    if (!k || !k_mean || !codes || !scales) return fail(PARO_EINVAL, "k, k_mean, codes and scales must not be NULL");
+    if (((uintptr_t)k | (uintptr_t)k_mean | (uintptr_t)codes) & 15) return fail(PARO_EINVAL, "k, k_mean and codes must be 16-byte aligned");
+    if (k == codes) return fail(PARO_EINVAL, "input and codes must not alias");
+    ReorderTable table;
+    if (int st = make_reorder_table(s, h_perm_ids, &table)) return st;
+    const dim3 grid((unsigned)kb, (unsigned)(s->B * s->nh));
+    if (dtype == PARO_F32)
+        launch_smoothed_shape<float>(s->block, s->d, bits, grid, (hipStream_t)stream, k, k_mean, codes, scales, (int)n, (int)kb, table, s->nh);
+    else
+        launch_smoothed_shape<uint16_t>(s->block, s->d, bits, grid, (hipStream_t)stream, k, k_mean, codes, scales, (int)n, (int)kb, table, s->nh);
+    return check_launch("paro_permute_quantize_smoothed");
 }

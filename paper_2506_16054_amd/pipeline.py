@@ -102,6 +102,22 @@ class ParoAttention:
         self.prepare_fused(q, k, v)
         return self.attend_fused()
 
+    # ---- optional pre-conditioning of K: the per-channel mean over the tokens is removed in the quantizer's loads
+    def prepare_fused_smooth_k(self, q, k, v) -> None:
+        """prepare_fused with paro_k_channel_mean + paro_permute_quantize_smoothed for K (integer K codes only)."""
+        s = self.s
+        fq, fk = self._fused_buffers()
+        if not hasattr(self, "k_mean"):
+            self.k_mean = torch.empty((s.B, s.nh, s.d), dtype=torch.float32, device=self.dev)
+        pb.paro_k_channel_mean(s, k, self.k_mean)
+        pb.paro_permute_quantize(s, self.bits_qk, pb.PARO_ROWS, self.perm_ids, q, fq, self.sq)
+        pb.paro_permute_quantize_smoothed(s, self.bits_qk, self.perm_ids, k, self.k_mean, fk, self.sk)
+        pb.paro_permute_quantize(s, self.bits_pv, pb.PARO_VT, self.perm_ids, v, self.vc, self.sv)
+
+    def run_fused_smooth_k(self, q, k, v):
+        self.prepare_fused_smooth_k(q, k, v)
+        return self.attend_fused()
+
     # ---- shortest form (block 64, 8-bit QK): Q is reordered and quantized inside the attention kernel,
     # by the workgroup that owns the row block; three launches
     @property

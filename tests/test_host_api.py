@@ -183,6 +183,25 @@ def test_fused_entry_points_validate_on_the_host():
     assert L.paro_sparse_attn_unpermuted(ctypes.byref(s), 8, 8, *args, 4, None, bad.ctypes.data, pb.PARO_F32, fake, None) == pb.PARO_EINVAL
 
 
+def test_k_smoothing_entry_points_validate_on_the_host():
+    L = pb.lib()
+    s = pb.make_shape(1, 2, 64, 2, 8, 8, 0, 32)
+    fake, other = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x2000)
+    ok = np.array([0, 5], np.uint8)
+    bad = np.array([0, 7], np.uint8)
+    assert L.paro_k_channel_mean(ctypes.byref(s), pb.PARO_F32, None, fake, None) == pb.PARO_EINVAL
+    assert L.paro_k_channel_mean(ctypes.byref(s), pb.PARO_F32, fake, None, None) == pb.PARO_EINVAL
+    assert L.paro_k_channel_mean(ctypes.byref(s), 5, fake, other, None) == pb.PARO_EINVAL
+    assert L.paro_k_channel_mean(ctypes.byref(s), pb.PARO_F32, ctypes.c_void_p(0x1008), other, None) == pb.PARO_EINVAL
+    sm = lambda dt, bits, perm, k, mean, codes, scales: L.paro_permute_quantize_smoothed(ctypes.byref(s), dt, bits, perm, k, mean, codes, scales, None)
+    assert sm(pb.PARO_F32, 8, None, fake, fake, other, fake) == pb.PARO_EINVAL               # no perm_ids
+    assert sm(pb.PARO_F32, 8, bad.ctypes.data, fake, fake, other, fake) == pb.PARO_EINVAL    # perm id out of range
+    assert sm(pb.PARO_F32, 16, ok.ctypes.data, fake, fake, other, fake) == pb.PARO_EINVAL    # integer codes only
+    assert sm(pb.PARO_F32, 8, ok.ctypes.data, fake, None, other, fake) == pb.PARO_EINVAL     # no mean
+    assert sm(pb.PARO_F32, 8, ok.ctypes.data, fake, fake, fake, fake) == pb.PARO_EINVAL      # codes alias the input
+    assert sm(9, 8, ok.ctypes.data, fake, fake, other, fake) == pb.PARO_EINVAL
+
+
 def test_row_schedule_is_a_permutation_heaviest_first_within_l2_groups():
     rng = np.random.default_rng(5)
     # headline shape: one head's K+V (2.25 MB) fills the L2 budget alone -> groups of one head
