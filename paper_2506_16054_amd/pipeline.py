@@ -154,9 +154,15 @@ class MaskPrefetcher:
         slot.free    recorded on the compute stream in ``release`` after that attention call; the
                      copy stream waits on it before it overwrites the slot.
 
+    ``lists_on_host=True`` trades host memory for device work: the record also holds the expanded column list
+    (4 bytes per live block instead of 1 bit per block), ``prefetch`` is the one transfer and no kernel runs on
+    the second stream at all.
+
     Both streams have the default priority.  No arithmetic happens here."""
 
-    def __init__(self, shape: pb.paro_shape, h_bitmasks: np.ndarray, h_row_orders=None, cap=None, device="cuda:0"):
+    def __init__(self, shape: pb.paro_shape, h_bitmasks: np.ndarray, h_row_orders=None, cap=None, device="cuda:0",
+                 lists_on_host: bool = False):
+        self.lists_on_host = bool(lists_on_host)
         self.s = shape
         self.dev = torch.device(device)
         self.k = pb.paro_nblocks(shape)
@@ -176,21 +182,23 @@ class MaskPrefetcher:
         align = lambda n: (n + 15) // 16 * 16
         self._off_ptr = align(nh * nbytes)
         self._off_ord = self._off_ptr + align(nh * (k + 1) * 4)
-        self._rec = self._off_ord + (align(n_order * 4) if ro is not None else 0)
+        self._off_col = self._off_ord + (align(n_order * 4) if ro is not None else 0)
+        lists = [pb.paro_mask_to_blocklist(nh, k, bm[t]) for t in range(self.T)]
+        nnz_max = max(1, max(int(ci.size) for _, ci in lists))
+        self.cap = int(cap) if cap is not None else nnz_max
+        if self.cap < nnz_max:
+            raise pb.ParoError(pb.PARO_EINVAL, "cap=%d is smaller than the longest block list (%d)" % (self.cap, nnz_max))
+        self._rec = self._off_col + (align(self.cap * 4) if self.lists_on_host else 0)
         host = np.zeros((self.T, self._rec), np.uint8)
-        nnz_max = 1
-        for t in range(self.T):
-            row_ptr, col_idx = pb.paro_mask_to_blocklist(nh, k, bm[t])
-            nnz_max = max(nnz_max, int(col_idx.size))
+        for t, (row_ptr, col_idx) in enumerate(lists):
             host[t, : nh * nbytes] = bm[t].reshape(-1)
             host[t, self._off_ptr: self._off_ptr + row_ptr.nbytes] = row_ptr.reshape(-1).view(np.uint8)
             if ro is not None:
                 host[t, self._off_ord: self._off_ord + ro[t].nbytes] = ro[t].view(np.uint8)
+            if self.lists_on_host:
+                host[t, self._off_col: self._off_col + col_idx.nbytes] = col_idx.view(np.uint8)
         self.h_records = torch.empty(host.shape, dtype=torch.uint8, pin_memory=True)
         self.h_records.copy_(torch.from_numpy(host))
-        self.cap = int(cap) if cap is not None else nnz_max
-        if self.cap < nnz_max:
-            raise pb.ParoError(pb.PARO_EINVAL, "cap=%d is smaller than the longest block list (%d)" % (self.cap, nnz_max))
         self.copy_stream = torch.cuda.Stream(self.dev)
         z = dict(device=self.dev)
         self.slots = []
@@ -201,7 +209,8 @@ class MaskPrefetcher:
                 "bitmask": rec[: nh * nbytes].view(nh, nbytes),
                 "row_ptr": rec[self._off_ptr: self._off_ptr + nh * (k + 1) * 4].view(torch.int32).view(nh, k + 1),
                 "row_order": None if ro is None else rec[self._off_ord: self._off_ord + n_order * 4].view(torch.int32),
-                "col_idx": torch.zeros((self.cap,), dtype=torch.int32, **z),
+                "col_idx": (rec[self._off_col: self._off_col + self.cap * 4].view(torch.int32) if self.lists_on_host
+                            else torch.zeros((self.cap,), dtype=torch.int32, **z)),
                 "ready": torch.cuda.Event(),
                 "free": torch.cuda.Event(),
             })
@@ -213,7 +222,8 @@ class MaskPrefetcher:
         with torch.cuda.stream(self.copy_stream):
             self.copy_stream.wait_event(sl["free"])
             sl["record"].copy_(self.h_records[t], non_blocking=True)
-            pb.paro_blocklist_cols_device(self.s.nh, self.k, sl["bitmask"], sl["row_ptr"], sl["col_idx"])
+            if not self.lists_on_host:
+                pb.paro_blocklist_cols_device(self.s.nh, self.k, sl["bitmask"], sl["row_ptr"], sl["col_idx"])
             sl["ready"].record(self.copy_stream)
 
     def acquire(self, slot: int):

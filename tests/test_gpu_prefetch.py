@@ -101,10 +101,11 @@ def test_columns_with_corrupt_offsets_stay_inside_the_list():
     assert np.all(got[:32] == -7) and np.all(got[32 + cap:] == -7)  # guard zones on both sides untouched
 
 
-def test_prefetched_sequence_is_bit_identical_to_host_built_lists():
+@pytest.mark.parametrize("lists_on_host", [False, True])
+def test_prefetched_sequence_is_bit_identical_to_host_built_lists(lists_on_host):
     """Five 'timesteps' with different masks through the two slots, two rounds without any host
     synchronisation in between: every output equals the one obtained with that mask's host-built
-    block list."""
+    block list - with the masks expanded on the device, and with the expanded lists kept on the host."""
     torch, pb = _mods()
     from paper_2506_16054_amd.pipeline import MaskPrefetcher, ParoAttention
 
@@ -123,7 +124,7 @@ def test_prefetched_sequence_is_bit_identical_to_host_built_lists():
     orders = np.stack([pb.paro_schedule_rows(s, w.bits_qk, w.bits_pv, pb.paro_mask_to_blocklist(w.nh, w.k, bm)[0]) for bm in bitmasks])
 
     pa = ParoAttention(s, perm_ids, bitmasks[0], w.bits_qk, w.bits_pv, torch.bfloat16)
-    pf = MaskPrefetcher(s, np.stack(bitmasks), orders)
+    pf = MaskPrefetcher(s, np.stack(bitmasks), orders, lists_on_host=lists_on_host)
     T = len(bitmasks)
     steps = 2 * T
     got = []
