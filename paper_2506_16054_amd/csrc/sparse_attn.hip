@@ -618,7 +618,10 @@ __device__ inline void lds_dma16(const uint8_t* base, unsigned lane_off, uint8_t
                                      (__attribute__((address_space(3))) void*)(lds_dst - OFFSET), 16, OFFSET, 0);
 }
 
-template <int PVBITS, typename OutT>
+// QSRC as in attn_i8_kernel: 0 = Q codes and scale from the quantizer; 1 (bf16) / 2 (fp32) = the unquantized Q in the
+// default token order, reordered and quantized here - the quantization group is the row block this wavefront owns,
+// so its absmax is one in-wave reduction.
+template <int PVBITS, typename OutT, int QSRC = 0>
 __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
     constexpr int BLK = 64, D = 64;
     constexpr int VPACK = PVBITS == 4 ? 2 : 1;
@@ -653,7 +656,7 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
     const unsigned vlane = n * (BLK / VPACK) + 16 * g;   // this lane's V^T piece of channel tile 0, inside a block
     const float* skp = a.sk + (size_t)bh * a.kblocks;
     const float* svp = a.sv + (size_t)bh * a.kblocks;
-    const float sq_i = a.sq[(size_t)bh * a.kblocks + i] * a.qk_scale;
+    float sq_i;
     int row[2];
     bool row_valid[2];
     unsigned invalid_row[2];
@@ -665,9 +668,72 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
         // or-ed into the bit pattern of a value <= 0 it gives a pattern at or above that of -inf: larger, as an
         // unsigned number, than the pattern of every value a real row can have
         invalid_row[H] = row_valid[H] ? 0u : 0xFF800000u;
-        const uint8_t* qrow = a.q + (head_rows + row[H]) * D + 16 * g;
+    }
+    if constexpr (QSRC == 0) {
+        sq_i = a.sq[(size_t)bh * a.kblocks + i] * a.qk_scale;
 #pragma unroll
-        for (int s = 0; s < 2; ++s) qf[H][s] = *(const v4i*)(qrow + 32 * s);
+        for (int H = 0; H < 2; ++H) {
+            const uint8_t* qrow = a.q + (head_rows + row[H]) * D + 16 * g;
+#pragma unroll
+            for (int s = 0; s < 2; ++s) qf[H][s] = *(const v4i*)(qrow + 32 * s);
+        }
+    } else {
+        // same arithmetic as the quantizer: absmax over the real rows of the block, scale = absmax / 127 in
+        // binary32, code = rint(fl32(x / scale))
+        using RawT = std::conditional_t<QSRC == 1, uint16_t, float>;
+        float x[2][2][16];  // this lane's slices of its two unquantized rows
+        float amax = 0.0f;
+#pragma unroll
+        for (int H = 0; H < 2; ++H) {
+            const RawT* qsrc = (const RawT*)a.q + ((size_t)bh * a.n_tokens + (row_valid[H] ? reorder_source(a.table, h, row[H]) : 0)) * D + 16 * g;
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                if (row_valid[H]) {
+                    if constexpr (QSRC == 1) {
+                        const uint4 lo = *(const uint4*)(qsrc + 32 * s), hi = *(const uint4*)(qsrc + 32 * s + 8);
+                        const unsigned wv[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            x[H][s][2 * e] = __uint_as_float(wv[e] << 16);
+                            x[H][s][2 * e + 1] = __uint_as_float(wv[e] & 0xffff0000u);
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float4 f = *(const float4*)(qsrc + 32 * s + 4 * e);
+                            x[H][s][4 * e] = f.x;
+                            x[H][s][4 * e + 1] = f.y;
+                            x[H][s][4 * e + 2] = f.z;
+                            x[H][s][4 * e + 3] = f.w;
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) x[H][s][e] = 0.0f;
+                }
+#pragma unroll
+                for (int e = 0; e < 16; ++e) amax = fmaxf(amax, fabsf(x[H][s][e]));
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+        const float scale = amax > 0.0f ? amax / 127.0f : 1.0f;
+        const GroupDivider quotient(scale);
+#pragma unroll
+        for (int H = 0; H < 2; ++H)
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    unsigned word = 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float r = fminf(fmaxf(rintf(quotient(x[H][s][4 * e4 + e])), -127.0f), 127.0f);
+                        word |= ((unsigned)(int)r & 0xffu) << (8 * e);
+                    }
+                    qf[H][s][e4] = (int)word;
+                }
+        sq_i = scale * a.qk_scale;
     }
 
     // column indices: 64 per fetch, one per lane, one chunk ahead
@@ -1469,8 +1535,22 @@ static void launch_rawq(paro_dtype out_dtype, const AttnArgs& a, hipStream_t st)
         hipLaunchKernelGGL((attn_i8_kernel<64, D, 8, PVBITS, uint16_t, QSRC>), grid, dim3(128), 0, st, a);
 }
 
+template <int PVBITS, int QSRC>
+static void launch_rawq_w64(paro_dtype out_dtype, const AttnArgs& a, hipStream_t st) {
+    dim3 grid((unsigned)(a.per_xcd * 8));
+    if (out_dtype == PARO_F32) hipLaunchKernelGGL((attn_i8_w64_kernel<PVBITS, float, QSRC>), grid, dim3(64), 0, st, a);
+    else hipLaunchKernelGGL((attn_i8_w64_kernel<PVBITS, uint16_t, QSRC>), grid, dim3(64), 0, st, a);
+}
+
 template <int QSRC>
 static void launch_rawq_shape(int d, int bits_pv, paro_dtype out_dtype, const AttnArgs& a, hipStream_t st) {
+    if constexpr (PARO_ATTN_SINGLE_WAVE) {
+        if (d == 64) {  // block 64 is a precondition of this entry point: the one-wavefront kernel applies
+            if (bits_pv == 8) launch_rawq_w64<8, QSRC>(out_dtype, a, st);
+            else launch_rawq_w64<4, QSRC>(out_dtype, a, st);
+            return;
+        }
+    }
     if (d == 64 && bits_pv == 8) launch_rawq<64, 8, QSRC>(out_dtype, a, st);
     else if (d == 64) launch_rawq<64, 4, QSRC>(out_dtype, a, st);
     else if (bits_pv == 8) launch_rawq<128, 8, QSRC>(out_dtype, a, st);
