@@ -223,22 +223,36 @@ __global__ __launch_bounds__(1024) void channel_mean_kernel(const InT* __restric
     const int rl = tid / CHUNKS;
     const InT* base = x + (size_t)blockIdx.x * n_tokens * D + cc * 8;
     double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int r0 = rl; r0 < n_tokens; r0 += 4 * ROWS) {
-        float v[4][8];
+    // With one workgroup per head, latency is what binds: a thread keeps 8 (bf16) or 4 (fp32) loads in flight, held as loaded
+    // (16 or 32 bytes each) and widened only when they are added.
+    constexpr int INFLIGHT = sizeof(InT) == 2 ? 8 : 4;
+    constexpr int WORDS = sizeof(InT) * 8 / 4;  // 32-bit words per 8 channels
+    for (int r0 = rl; r0 < n_tokens; r0 += INFLIGHT * ROWS) {
+        unsigned raw[INFLIGHT][WORDS];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < INFLIGHT; ++u) {
             const int r = r0 + u * ROWS;
             if (r < n_tokens) {
-                load8<InT>(base + (size_t)r * D, v[u]);
+                const uint4* src = (const uint4*)(base + (size_t)r * D);
+#pragma unroll
+                for (int q = 0; q < WORDS / 4; ++q) {
+                    const uint4 t = src[q];
+                    raw[u][4 * q] = t.x; raw[u][4 * q + 1] = t.y; raw[u][4 * q + 2] = t.z; raw[u][4 * q + 3] = t.w;
+                }
             } else {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[u][e] = 0.0f;
+                for (int q = 0; q < WORDS; ++q) raw[u][q] = 0u;
             }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < INFLIGHT; ++u)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] += (double)v[u][e];
+            for (int e = 0; e < 8; ++e) {
+                float f;
+                if constexpr (sizeof(InT) == 2) f = __uint_as_float((e & 1) ? (raw[u][e >> 1] & 0xffff0000u) : (raw[u][e >> 1] << 16));
+                else f = __uint_as_float(raw[u][e]);
+                acc[e] += (double)f;
+            }
     }
     // lanes of a wavefront that own the same chunk are CHUNKS apart
 #pragma unroll
