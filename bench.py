@@ -396,6 +396,9 @@ def main():
         rawq_ms = (time.perf_counter() - t3) * 1e3 / args.steps
     attn_ms = sorted(a.elapsed_time(b) for a, b in ev)
     attn_avg = sum(attn_ms) / len(attn_ms)
+    # the quantizer launch of step i lies between the end of attention i-1 and the start of attention i (gap included)
+    quant_ms = sorted(ev[i - 1][1].elapsed_time(ev[i][0]) for i in range(1, len(ev)))
+    quant_avg = sum(quant_ms) / len(quant_ms) if quant_ms else None
 
     prefetch = None if args.no_prefetch else prefetch_overhead(args, w, s, pa, perm_ids, q, k, v)
 
@@ -412,6 +415,20 @@ def main():
     rec = recorded_counters(w, live) if quantized else {"valu_instructions": None, "traffic": None, "stale": None}
     n_cus = int(torch.cuda.get_device_properties(0).multi_processor_count)
     issue = valu_issue_roofline(w, live, attn_avg, n_cus) if quantized else None
+    # second kernel of a step: the one-grid quantizer, bound by HBM (Q, K, V read once, their codes written once)
+    in_bytes = 2 if w.dtype == "bf16" else 4
+    quant_bytes = int(w.B * w.nh * (3 * w.N * w.d * in_bytes + w.npad * w.d * (2 * qk_bytes + v_bytes)))
+    quant_roofline = None
+    if quant_avg:
+        copy_rate = probe.sustained_copy_rate(2 if in_bytes == 2 else 1)
+        quant_roofline = {
+            "kernel": "paro_permute_quantize_qkv", "bound": "hbm", "achieved": quant_bytes / (quant_avg * 1e-3) / 1e9, "peak": 8000.0,
+            "unit": "GB/s", "frac": quant_bytes / (quant_avg * 1e-3) / 8e12, "ms_avg": quant_avg, "ms_min": quant_ms[0],
+            "algorithmic_bytes": quant_bytes, "plain_copy_sustained": copy_rate * 1e3,
+            "frac_of_plain_copy": quant_bytes / (quant_avg * 1e-3) / 1e12 / copy_rate,
+            "note": "time from the end of one attention launch to the start of the next (HIP events), i.e. the quantizer launch and "
+                    "its two launch gaps; plain_copy_sustained = a streaming copy with the same read:write mix, measured in this run",
+        }
     out = {
         "metric": "dense_equivalent_TOPS",
         "value": dense_ops / (ms_per_step * 1e-3) / 1e12,
@@ -459,6 +476,8 @@ def main():
         issue["recorded_SQ_INSTS_VALU_per_launch"] = rec["valu_instructions"]
         issue["profiles_record_stale"] = rec["stale"]
         out["roofline_valu_issue"] = issue
+    if quant_roofline is not None:
+        out["roofline_quantizer"] = quant_roofline
     if prefetch is not None:
         out["mask_prefetch"] = prefetch
     if cpu is not None:

@@ -4,6 +4,8 @@
 //   paro_probe_issue  what one wavefront instruction of a given kind costs a SIMD, in shader-clock
 //                     cycles, with 1..4 wavefronts resident per SIMD, alone or next to a wavefront
 //                     that issues matrix instructions back to back;
+//   paro_probe_copy   the rate of a plain streaming copy (1:1 and 2:1 read:write), the yardstick of the
+//                     path's bandwidth-bound kernels;
 //   paro_probe_block  a register-only replica of the vector-ALU and matrix work of ONE live block of
 //                     the INT8 attention kernel (no global memory, LDS or barrier), to tell issue
 //                     cost from memory and synchronisation cost.
@@ -586,6 +588,23 @@ __global__ __launch_bounds__(256) void pair_kernel(int iters, WaveTimes* __restr
 #undef PAIR_FENCE
 }
 
+// ---- plain streaming copy: what HBM sustains for the byte mix of the path's bandwidth-bound kernels --------------
+// Every thread reads 16 bytes per step, grid-stride, and writes 16 bytes for every WRITE_EVERY-th read (1: a copy,
+// 2: the quantizer's mix of two bytes read per byte written; the value written folds the reads in between).
+template <int WRITE_EVERY>
+__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, long long n_read) {
+    const long long stride = (long long)gridDim.x * blockDim.x * WRITE_EVERY;
+    for (long long i = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * WRITE_EVERY; i + WRITE_EVERY <= n_read; i += stride) {
+        uint4 v = src[i];
+#pragma unroll
+        for (int u = 1; u < WRITE_EVERY; ++u) {
+            const uint4 t = src[i + u];
+            v.x ^= t.x; v.y += t.y; v.z ^= t.z; v.w += t.w;
+        }
+        dst[i / WRITE_EVERY] = v;
+    }
+}
+
 template <int KIND>
 int launch_issue(int cus, int w, int iters, int with_mfma, WaveTimes* out, int* sink, hipStream_t st) {
     if (with_mfma)
@@ -627,6 +646,20 @@ int64_t paro_probe_mfma(int bits, int iters, int32_t* out, int64_t out_len, void
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return hip_failed("launch of probe_mfma_kernel", e);
     const int64_t per_instr = bits == 8 ? 2LL * 32 * 32 * 32 : 2LL * 32 * 32 * 16;
     return (int64_t)kProbeGroups * 4 * iters * 4 * per_instr;
+}
+
+// Streaming-copy probe: reads n_read 16-byte words of src and writes n_read / write_every of them to dst
+// (write_every 1 or 2), `groups` workgroups of 256 threads.  Returns bytes moved (read + written) or a negative status.
+//   src  [n_read * 16 bytes] (device);  dst  [n_read / write_every * 16 bytes] (device)
+int64_t paro_probe_copy(const void* src, void* dst, int64_t n_read, int write_every, int groups, void* stream) {
+    if (!src || !dst || n_read < 2 || (write_every != 1 && write_every != 2) || groups < 1 || groups > (1 << 20)) return kErrInval;
+    if (write_every == 1)
+        hipLaunchKernelGGL(copy_kernel<1>, dim3(groups), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst, (long long)n_read);
+    else
+        hipLaunchKernelGGL(copy_kernel<2>, dim3(groups), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst, (long long)n_read);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return hip_failed("launch of copy_kernel", e);
+    const int64_t reads = n_read / write_every * write_every;
+    return 16 * (reads + reads / write_every);
 }
 
 const char* paro_probe_last_error(void) { return g_error; }

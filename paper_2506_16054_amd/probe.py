@@ -45,6 +45,8 @@ def lib() -> ctypes.CDLL:
         L.paro_probe_issue.argtypes = [i32, i32, i32, i32, i32, vp, vp, i64, vp]
         L.paro_probe_block.argtypes = [i32, i32, i32, i32, vp, vp, i64, vp]
         L.paro_probe_pair.argtypes = [i32, i32, i32, vp, vp, i64, vp]
+        L.paro_probe_copy.restype = i64
+        L.paro_probe_copy.argtypes = [vp, vp, i64, i32, i32, vp]
         _lib = L
     return _lib
 
@@ -86,6 +88,35 @@ def sustained_mfma_rate(bits: int) -> float:
     e1.record()
     torch.cuda.synchronize()
     return ops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
+def sustained_copy_rate(write_every: int, mbytes_read: int = 512, groups_per_cu: int = 8) -> float:
+    """TB/s (bytes read + written per second) of a plain streaming copy: write_every 1 = one byte written per byte
+    read, 2 = one per two (the quantizer's mix).  Best of the workgroup counts tried."""
+    import torch
+
+    n_read = mbytes_read * (1 << 20) // 16
+    src = torch.empty(n_read * 16, dtype=torch.uint8, device="cuda:0").fill_(3)
+    dst = torch.empty(n_read * 16 // write_every, dtype=torch.uint8, device="cuda:0")
+    best = 0.0
+    for per_cu in (groups_per_cu, 2 * groups_per_cu, 4 * groups_per_cu):
+        groups = compute_units() * per_cu
+
+        def launch():
+            moved = lib().paro_probe_copy(src.data_ptr(), dst.data_ptr(), n_read, write_every, groups, _stream())
+            if moved < 0:
+                raise RuntimeError("paro_probe_copy failed with status %d: %s" % (moved, lib().paro_probe_last_error().decode()))
+            return moved
+
+        for _ in range(3):
+            launch()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        moved = sum(launch() for _ in range(10))
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, moved / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    return best
 
 
 def _times(launch, per_wave_work: float, timed_per_simd: int):
@@ -187,3 +218,6 @@ def markdown(tab: dict) -> str:
 
 if __name__ == "__main__":
     sys.stdout.write(markdown(issue_table()) + "\n")
+    sys.stdout.write("\n| plain streaming copy, 512 MB read | TB/s (read + written) |\n|---|---|\n")
+    sys.stdout.write("| one byte written per byte read | %.2f |\n| one byte written per two read (the quantizer's mix) | %.2f |\n"
+                     % (sustained_copy_rate(1), sustained_copy_rate(2)))

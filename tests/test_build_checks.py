@@ -92,6 +92,6 @@ def test_probe_library_exports_what_bench_calls():
     assert os.path.exists(LIBPATH), "build with python -m paper_2506_16054_amd.build"
     lib = ctypes.CDLL(LIBPATH)
     for name in ("paro_probe_mfma", "paro_probe_last_error", "paro_probe_issue_kinds", "paro_probe_issue_name", "paro_probe_issue",
-                 "paro_probe_block", "paro_probe_pair"):
+                 "paro_probe_block", "paro_probe_pair", "paro_probe_copy"):
         assert hasattr(lib, name), name
     assert lib.paro_probe_issue_kinds() >= 22
