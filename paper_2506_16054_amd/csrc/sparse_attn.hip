@@ -996,7 +996,9 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
 // line the eight 16-byte pieces are stored at position (piece ^ line % 8): the reads of 16 lanes that walk
 // down a column of pieces then spread over all banks.  Two K slots and two V slots; ONE barrier per block,
 // after the wavefront has written its share of the tile exponent and waited for its own requests: behind
-// it K_{t+2} may overwrite K_t (all K_t reads precede the barrier) and V_{t+1} may overwrite V_{t-1}.
+// it K_{t+2} may overwrite K_t (all K_t reads precede the barrier) and V_{t+1} may overwrite V_{t-1}.  K_{t+2}
+// is requested right behind the barrier; V_{t+1} only after the V_t fragments have been read, because the
+// compiler makes every read of the V ring wait for all requests into that ring issued before it.
 // Arithmetic per block as in attn_i8_kernel.
 // -------------------------------------------------------------------------------------------
 #ifndef PARO_ATTN_Q16
@@ -1172,8 +1174,8 @@ __global__ __launch_bounds__(256, 3) void attn_i8_q16_kernel(AttnArgs a) {
         // barrier both tiles and all four exponents are whole, K_t has been read by all and V_{t-1} is consumed
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
-        if (t + 1 < cnt) request_v(j1, (t + 1) & 1);
         if (t + 2 < cnt) request_k(j2, t & 1);
+        const int j_v = j1;
         const float e = __uint_as_float(min(min(tile_e[t & 1][0], tile_e[t & 1][1]), min(tile_e[t & 1][2], tile_e[t & 1][3])));
         // the next step's column, scales and the column after it (scalar work, hidden behind the vector work below)
         j0 = j1;
@@ -1234,6 +1236,7 @@ __global__ __launch_bounds__(256, 3) void attn_i8_q16_kernel(AttnArgs a) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[ct][r] = fmaf(int_result(o[r]), sv_eff, acc[ct][r]);
         }
+        if (t + 1 < cnt) request_v(j_v, (t + 1) & 1);
     };
 
     constexpr bool FOLDABLE = PARO_FOLD_LOGIT_BIAS;
