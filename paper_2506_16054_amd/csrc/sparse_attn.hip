@@ -1421,17 +1421,28 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? 3 : 2)) void attn_bf16_kernel(A
                 for (int r = 0; r < 16; ++r)
                     if (32 * T + 8 * (r >> 2) + 4 * g + (r & 3) >= nkeys) sacc[T][r] = -INFINITY;
         }
-        float part[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        auto row_max = [&]() {  // maximum over the block's keys of this lane's query, in both of its lanes
+            float part[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+            for (int T = 0; T < KT; ++T)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) part[r & 3] = fmaxf(part[r & 3], sacc[T][r]);
+            const float mx = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_int(mx), __float_as_int(mx), false, false);
+            return fmaxf(__int_as_float((int)sw[0]), __int_as_float((int)sw[1]));
+        };
+        // a row without a reference yet (first block, or nothing but masked keys so far) takes its block maximum
+        if (__builtin_amdgcn_ballot_w64(m_ref == -INFINITY) != 0) {
+            const float ymax = c * row_max();
+            if (m_ref == -INFINITY) m_ref = ymax;
+        }
+        // y = c S - m_ref, the exponent of P, FIRST, in place of S: its maximum tells whether the row has climbed past
+        // its reference (results of an fma need no NaN quieting before a maximum, raw matrix results would)
 #pragma unroll
         for (int T = 0; T < KT; ++T)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) part[r & 3] = fmaxf(part[r & 3], sacc[T][r]);
-        float mx = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
-        {
-            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_int(mx), __float_as_int(mx), false, false);
-            mx = fmaxf(__int_as_float((int)sw[0]), __int_as_float((int)sw[1]));
-        }
-        const float ymax = c * mx;
+            for (int r = 0; r < 16; ++r) sacc[T][r] = fmaf(sacc[T][r], c, -m_ref);
+        const float climb = row_max();  // row maximum - reference
         __syncthreads();
         lstore_v(0);                      // V_t (loaded one block ago)
         if (t + 1 < cnt) lstore_k(0);     // K_{t+1}
@@ -1442,18 +1453,20 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? 3 : 2)) void attn_bf16_kernel(A
             cols_nxt = load_cols(cur_chunk + 1);
         }
         if (t + 2 < cnt) gload_k(t + 2);
-        if (m_ref == -INFINITY) m_ref = ymax;
-        if (__builtin_amdgcn_ballot_w64(ymax - m_ref > 64.0f) != 0) {
-            const float up = fmaxf(ymax, m_ref);
-            const float down = __builtin_amdgcn_exp2f(m_ref - up);
+        if (__builtin_amdgcn_ballot_w64(climb > 64.0f) != 0) {
+            const float up = fmaxf(climb, 0.0f);  // rows that have not climbed keep their reference
+            const float down = __builtin_amdgcn_exp2f(-up);
             l *= down;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[dt][r] *= down;
-            m_ref = up;
+#pragma unroll
+            for (int T = 0; T < KT; ++T)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sacc[T][r] -= up;
+            m_ref += up;
         }
-        const float m_new = m_ref;
 
         float rs = 0.0f;
         v8bf pf[KT][2];
@@ -1463,8 +1476,8 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? 3 : 2)) void attn_bf16_kernel(A
             for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int e2 = 0; e2 < 4; ++e2) {
-                    const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[T][8 * u + 2 * e2], c, -m_new));
-                    const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[T][8 * u + 2 * e2 + 1], c, -m_new));
+                    const float p0 = __builtin_amdgcn_exp2f(sacc[T][8 * u + 2 * e2]);
+                    const float p1 = __builtin_amdgcn_exp2f(sacc[T][8 * u + 2 * e2 + 1]);
                     rs += p0 + p1;
                     const v2bf pb = __builtin_convertvector(v2f{p0, p1}, v2bf);
                     pf[T][u][2 * e2] = pb[0];
@@ -1503,6 +1516,230 @@ __global__ __launch_bounds__(BLK * 2, (D == 64 ? 3 : 2)) void attn_bf16_kernel(A
     }
 }
 
+// -------------------------------------------------------------------------------------------
+// bf16 mode at d = 64, block 64: FOUR wavefronts of 16 queries per row block on v_mfma_f32_16x16x32_bf16, built like
+// attn_i8_q16_kernel.  A bf16 K tile at d = 64 (64 rows of 128 bytes) and a bf16 V^T tile (64 channel rows of 128
+// bytes) have the geometry of the 8-bit tiles at d = 128, so the tiles go to LDS the same way (global_load_lds,
+// a quarter per wavefront, pieces of a line at position piece ^ line % 8, two K and two V slots, one barrier per
+// block).  P is not quantized: nothing is exchanged between the wavefronts, the exponentials are taken against the
+// row's fixed reference and O^T accumulates in the matrix accumulators themselves (16 registers), so the vector
+// work per block is the logits' alone.
+// Row 4 G + r of S^T tile T is the key whose PARO_VT slot is 32 (T >> 1) + 8 G + 4 (T & 1) + r - the slot that
+// element 4 (T & 1) + r of lane group G covers in contraction step T >> 1 of the PV product - i.e. token
+// 32 (T >> 1) + 8 (T & 1) + 16 (G & 1) + 4 (G >> 1) + r of the block.
+// -------------------------------------------------------------------------------------------
+#ifndef PARO_BF16_Q16
+#define PARO_BF16_Q16 1
+#endif
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__device__ inline float quad_rows_fmax(float x) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_int(x), __float_as_int(x), false, false);
+    const float y = fmaxf(__int_as_float((int)r[0]), __int_as_float((int)r[1]));
+    const auto q = __builtin_amdgcn_permlane32_swap(__float_as_int(y), __float_as_int(y), false, false);
+    return fmaxf(__int_as_float((int)q[0]), __int_as_float((int)q[1]));
+}
+
+template <typename OutT>
+__global__ __launch_bounds__(256, 4) void attn_bf16_q16_kernel(AttnArgs a) {
+    constexpr int BLK = 64, D = 64;
+    constexpr int KS = D / 32;     // contraction steps of QK^T (32 channels each)
+    constexpr int US = BLK / 32;   // contraction steps of PV (32 slots each)
+    constexpr int CT = D / 16;     // 16-channel tiles of the output
+    constexpr int TILE = BLK * D * 2;  // bytes of a K tile and of a V^T tile
+    static_assert(TILE == 8192, "the tile transfer below moves eight 1 KB pieces");
+    __shared__ __attribute__((aligned(16))) uint8_t kring[2][TILE];
+    __shared__ __attribute__((aligned(16))) uint8_t vring[2][TILE];
+
+    const int wg = blockIdx.x;
+    const int logical = (wg & 7) * a.per_xcd + (wg >> 3);
+    if (logical >= a.total_wg) return;
+    const int item = a.row_order ? min(max(a.row_order[logical], 0), a.total_wg - 1) : logical;
+    const int bh = item / a.kblocks;
+    const int i = item - bh * a.kblocks;
+    const int h = bh % a.nh;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15;
+    const int G = lane >> 4;
+
+    const int* rp = a.row_ptr + (size_t)h * (a.kblocks + 1) + i;
+    const int beg = __builtin_amdgcn_readfirstlane(min(max(rp[0], 0), a.nnz));
+    const int end = __builtin_amdgcn_readfirstlane(min(max(rp[1], beg), a.nnz));
+    const int cnt = end - beg;
+    const int* cols = a.col_idx + beg;
+    if (2 * cnt > a.kblocks) __builtin_amdgcn_s_setprio(2);
+
+    const size_t head_rows = (size_t)bh * a.kblocks * BLK;
+    const uint8_t* kbase = a.k + head_rows * D * 2;
+    const uint8_t* vbase = a.v + head_rows * D * 2;
+    const float c = a.qk_scale;
+    const int row = i * BLK + 16 * w + n;  // this lane's query, in the reordered sequence
+    const bool row_valid = row < a.n_tokens;
+    v8bf qf[KS];
+    {
+        const uint8_t* qrow = a.q + (head_rows + row) * D * 2 + 16 * G;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qf[s] = *(const v8bf*)(qrow + 64 * s);
+    }
+    // tile transfer as in attn_i8_q16_kernel
+    const unsigned fill_lane = 2048u * w + 128u * (lane >> 3) + 16u * ((lane & 7) ^ (lane >> 3));
+    // K fragment of tile T, step s: row 32 (T >> 1) + 8 (T & 1) + 16 ((n >> 2) & 1) + 4 (n >> 3) + (n & 3), piece 4 s + G
+    const unsigned krow = 16 * ((n >> 2) & 1) + 4 * (n >> 3) + (n & 3);
+    unsigned kread[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) kread[s] = 128u * krow + 16u * ((4 * s + G) ^ (krow & 7));
+    // V^T fragment of channel tile ct, step u: PARO_VT row 16 ct + n, piece 4 u + G
+    unsigned vread[US];
+#pragma unroll
+    for (int u = 0; u < US; ++u) vread[u] = 128u * n + 16u * ((4 * u + G) ^ (n & 7));
+
+    auto load_cols = [&](int chunk) {
+        const int idx = min(chunk * 64 + lane, cnt - 1);
+        return cnt > 0 && chunk * 64 < cnt ? min(max(cols[idx], 0), a.kblocks - 1) : 0;
+    };
+    int cols_cur = load_cols(0), cols_nxt = load_cols(1);
+    int cur_chunk = 0;
+    auto col_at = [&](int u) {  // u advances by one per call
+        if ((u & 63) == 0 && u > 0) {
+            cols_cur = cols_nxt;
+            ++cur_chunk;
+            cols_nxt = load_cols(cur_chunk + 1);
+        }
+        return __builtin_amdgcn_readlane(cols_cur, u & 63);
+    };
+    auto request_k = [&](int j, int slot) {
+        const uint8_t* kp = kbase + (size_t)j * TILE;
+        lds_dma16<0>(kp, fill_lane, &kring[slot][2048 * w]);
+        lds_dma16<1024>(kp, fill_lane, &kring[slot][2048 * w + 1024]);
+    };
+    auto request_v = [&](int j, int slot) {
+        const uint8_t* vp = vbase + (size_t)j * TILE;
+        lds_dma16<0>(vp, fill_lane, &vring[slot][2048 * w]);
+        lds_dma16<1024>(vp, fill_lane, &vring[slot][2048 * w + 1024]);
+    };
+
+    float m_ref = -INFINITY, l = 0.0f;
+    v4f acc[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) acc[ct] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+
+    int j0 = 0, j1 = 0, j2 = 0;  // columns of the steps t, t + 1, t + 2
+    if (cnt > 0) {
+        j0 = col_at(0);
+        request_k(j0, 0);
+        request_v(j0, 0);
+        if (cnt > 1) {
+            j1 = col_at(1);
+            request_k(j1, 1);
+        }
+        if (cnt > 2) j2 = col_at(2);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    __syncthreads();
+    const int tail_block = (a.n_tokens % BLK) != 0 ? a.kblocks - 1 : -1;  // the column block with padded keys, if any
+
+    for (int t = 0; t < cnt; ++t) {
+        const uint8_t* kslot = &kring[t & 1][0];
+        const uint8_t* vslot = &vring[t & 1][0];
+        // ---- S^T = K_j Q_i^T: four 16-key tiles
+        v4f sacc[4];
+#pragma unroll
+        for (int T = 0; T < 4; ++T) {
+            sacc[T] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                sacc[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const v8bf*)(kslot + 4096 * (T >> 1) + 1024 * (T & 1) + kread[s]), qf[s],
+                                                                  sacc[T], 0, 0, 0);
+        }
+        if (j0 == tail_block) {  // keys past N never receive probability mass
+            const int nkeys = a.n_tokens - (a.kblocks - 1) * BLK;
+#pragma unroll
+            for (int T = 0; T < 4; ++T)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (32 * (T >> 1) + 8 * (T & 1) + 16 * (G & 1) + 4 * (G >> 1) + r >= nkeys) sacc[T][r] = -INFINITY;
+        }
+        // a row without a reference yet (first block, or nothing but masked keys so far) takes its block maximum
+        if (__builtin_amdgcn_ballot_w64(m_ref == -INFINITY) != 0) {
+            float part[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part[r] = fmaxf(fmaxf(sacc[0][r], sacc[1][r]), fmaxf(sacc[2][r], sacc[3][r]));
+            const float ymax = c * quad_rows_fmax(fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3])));
+            if (m_ref == -INFINITY) m_ref = ymax;
+        }
+        // ---- y = c S - m_ref, the exponent of P, FIRST: its maximum tells whether the row has climbed past its
+        // reference (results of an fma need no NaN quieting before a maximum, raw matrix results would)
+        float p[4][4];
+#pragma unroll
+        for (int T = 0; T < 4; ++T)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) p[T][r] = fmaf(sacc[T][r], c, -m_ref);
+        float part[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) part[r] = fmaxf(fmaxf(p[0][r], p[1][r]), fmaxf(p[2][r], p[3][r]));
+        const float climb = quad_rows_fmax(fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3])));  // row maximum - reference
+        // ---- this wavefront's requests have landed; behind the barrier both tiles are whole, K_t has been read by
+        // all and V_{t-1} is consumed
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (t + 2 < cnt) request_k(j2, t & 1);
+        const int j_v = j1;
+        j0 = j1;
+        j1 = j2;
+        if (t + 3 < cnt) j2 = col_at(t + 3);
+
+        if (__builtin_amdgcn_ballot_w64(climb > 64.0f) != 0) {
+            const float up = fmaxf(climb, 0.0f);  // rows that have not climbed keep their reference
+            const float down = __builtin_amdgcn_exp2f(-up);
+            l *= down;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[ct][r] *= down;
+#pragma unroll
+            for (int T = 0; T < 4; ++T)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) p[T][r] -= up;
+            m_ref += up;
+        }
+        // ---- P = 2^y, its row sum in fp32, and P rounded to bf16 as B operand: element 4 (T & 1) + r of step T >> 1
+#pragma unroll
+        for (int T = 0; T < 4; ++T)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) p[T][r] = __builtin_amdgcn_exp2f(p[T][r]);
+        l += ((p[0][0] + p[0][1]) + (p[0][2] + p[0][3])) + ((p[1][0] + p[1][1]) + (p[1][2] + p[1][3])) +
+             (((p[2][0] + p[2][1]) + (p[2][2] + p[2][3])) + ((p[3][0] + p[3][1]) + (p[3][2] + p[3][3])));
+        v8bf pf[US];
+#pragma unroll
+        for (int u = 0; u < US; ++u)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                for (int e2 = 0; e2 < 2; ++e2) {
+                    const v2bf pb = __builtin_convertvector(v2f{p[2 * u + hh][2 * e2], p[2 * u + hh][2 * e2 + 1]}, v2bf);
+                    pf[u][4 * hh + 2 * e2] = pb[0];
+                    pf[u][4 * hh + 2 * e2 + 1] = pb[1];
+                }
+        // ---- O^T += V_j^T P^T, accumulated in the matrix accumulators
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int u = 0; u < US; ++u)
+                acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const v8bf*)(vslot + 2048 * ct + vread[u]), pf[u], acc[ct], 0, 0, 0);
+        if (t + 1 < cnt) request_v(j_v, (t + 1) & 1);
+    }
+
+    const float l_tot = quad_rows_sum(l);
+    const float inv = (row_valid && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
+    const long long ooff = out_row_offset<D>(a, bh, h, head_rows, row, row_valid);
+    if (ooff >= 0) {
+        OutT* orow = (OutT*)a.op + ooff + 4 * G;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) store4(orow + 16 * ct, acc[ct][0] * inv, acc[ct][1] * inv, acc[ct][2] * inv, acc[ct][3] * inv);
+    }
+}
+
 template <int BLK, int D, typename OutT>
 static int launch_bf16_t(const AttnArgs& a, hipStream_t st) {
     constexpr int bytes = Bf16Cfg<BLK, D>::LDS_BYTES;
@@ -1513,6 +1750,12 @@ static int launch_bf16_t(const AttnArgs& a, hipStream_t st) {
 
 template <typename OutT>
 static int launch_bf16(int blk, int d, const AttnArgs& a, hipStream_t st) {
+    if constexpr (PARO_BF16_Q16) {
+        if (blk == 64 && d == 64) {  // four wavefronts of 16 queries per row block
+            hipLaunchKernelGGL((attn_bf16_q16_kernel<OutT>), dim3((unsigned)(a.per_xcd * 8)), dim3(256), 0, st, a);
+            return PARO_OK;
+        }
+    }
     if (blk == 64 && d == 64) return launch_bf16_t<64, 64, OutT>(a, st);
     if (blk == 64 && d == 128) return launch_bf16_t<64, 128, OutT>(a, st);
     if (blk == 32 && d == 64) return launch_bf16_t<32, 64, OutT>(a, st);

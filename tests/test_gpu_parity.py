@@ -346,8 +346,9 @@ def test_row_maximum_climbing_hundreds_of_octaves(bits):
         # With fp32 output the error left is that of the arithmetic.  With 8-bit P codes the kernel forms the
         # exponent as c*(B + S) + offset: the offset's rounding grows with the logit scale c (here the logits
         # span hundreds of octaves, several times a real layer's), flips more near-tie codes, and is the
-        # larger part of what is left; the other modes keep the exact exponent.
-        assert st["rel_l2"] < (3e-3 if bits == 8 else 1e-3)
+        # larger part of what is left; the 16-bit mode keeps the exact exponent and rounds P to bf16 (2^-9 per
+        # element, and on these rows a handful of keys carry the whole sum).
+        assert st["rel_l2"] < (3e-3 if bits == 8 else 2e-3)
 
 
 @pytest.mark.parametrize("scale", [1e-3, 1e-6, 30.0])
