@@ -95,3 +95,16 @@ def test_probe_library_exports_what_bench_calls():
                  "paro_probe_block", "paro_probe_pair", "paro_probe_copy"):
         assert hasattr(lib, name), name
     assert lib.paro_probe_issue_kinds() >= 22
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The whole build runs on one GPU; the bench says so instead of timing anything (no GPU is touched)."""
+    import os
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr + r.stdout
+    assert not r.stdout.strip().startswith("{")
