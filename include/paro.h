@@ -125,7 +125,10 @@ int paro_check_row_order(const paro_shape* s, const int32_t* h_order);
  * to the 8 XCDs in 8 contiguous ranges; inside a range, row blocks are sorted by descending live
  * count within groups of consecutive heads whose K and V operands fit one L2 (4 MB) together (so
  * the reordering never evicts the K/V tiles being reused); a range whose heads all fit together is
- * one group.  bits_* size that footprint.  Host only. */
+ * one group.  A range of several groups keeps its lightest row blocks (half as many as the XCD
+ * holds workgroups, at most a quarter of the range) out of the groups and starts them last, heaviest
+ * first: the launch ends when the last-started row blocks are done, and these are the shortest.
+ * bits_* size the footprint and, with d and block, name the kernel.  Host only. */
 int paro_schedule_rows(const paro_shape* s, int bits_qk, int bits_pv, const int32_t* h_row_ptr,
                        int32_t* h_order);
 

@@ -2,6 +2,8 @@
 
     lib/libparo.so        the product library (everything include/paro.h declares)
     lib/libparo_probe.so  measurement aids of bench.py (csrc/probe/): matrix-rate and instruction-issue probes
+    lib/libparo_timeline.so  the product library with sparse_attn.hip compiled under -DPARO_TIMELINE=1 (every wavefront of
+                          the attention kernels records its start and end clock; read by `probe --timeline`)
 
     python -m paper_2506_16054_amd.build
 """
@@ -19,6 +21,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIBDIR = os.path.join(PKG, "lib")
 LIBPATH = os.path.join(LIBDIR, "libparo.so")
 PROBE_LIBPATH = os.path.join(LIBDIR, "libparo_probe.so")
+TIMELINE_LIBNAME = "libparo_timeline.so"
 SOURCES = ("host_api.cpp", "permute.hip", "quantize.hip", "blocklist.hip", "calibrate.hip", "sparse_attn.hip")
 PROBE_SOURCES = ("probe/issue_probe.hip",)
 
@@ -52,8 +55,8 @@ def spilling_kernels(remarks: str):
     return out
 
 
-def _compile(src: str, extra, objdir: str = LIBDIR) -> str:
-    obj = os.path.join(objdir, os.path.splitext(os.path.basename(src))[0] + ".o")
+def _compile(src: str, extra, objdir: str = LIBDIR, tag: str = "") -> str:
+    obj = os.path.join(objdir, os.path.splitext(os.path.basename(src))[0] + tag + ".o")
     device = src.endswith(".hip")
     report = ["-Rpass-analysis=kernel-resource-usage"] if device else []
     cmd = [hipcc(), *HIPCC_FLAGS, *report, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
@@ -160,12 +163,16 @@ def build_library(extra_flags=(), verbose: bool = True, out: str = LIBPATH, prob
     srcs = SOURCES + (PROBE_SOURCES if probe_out else ())
     with ThreadPoolExecutor(max_workers=4) as ex:
         counts = ex.submit(write_loop_counts, list(extra_flags), objdir)
+        timeline = ex.submit(_compile, "sparse_attn.hip", [*extra_flags, "-DPARO_TIMELINE=1"], objdir, "_timeline") if probe_out else None
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags), objdir), srcs))
         counts.result()
+        timeline_obj = timeline.result() if timeline else None
     _link(out, objs[: len(SOURCES)])
     if probe_out:
         os.makedirs(os.path.dirname(probe_out), exist_ok=True)
         _link(probe_out, objs[len(SOURCES):])
+        others = [o for o, src in zip(objs, SOURCES) if src != "sparse_attn.hip"]
+        _link(os.path.join(os.path.dirname(probe_out), TIMELINE_LIBNAME), others + [timeline_obj])
     if verbose:
         print("built", out, probe_out or "")
     return out

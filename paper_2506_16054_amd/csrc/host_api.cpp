@@ -216,25 +216,48 @@ int paro_schedule_rows(const paro_shape* s, int bits_qk, int bits_pv, const int3
     const int64_t kv_bytes = k * s->block * (int64_t)s->d * (bits_qk + bits_pv) / 8;
     const int64_t l2_budget = 4 << 20;
     const int64_t window = std::max<int64_t>(1, l2_budget / std::max<int64_t>(kv_bytes, 1));
-    std::vector<int32_t> ids;
+    // Workgroups one XCD holds at a time (32 compute units x 8 one-wavefront workgroups of the d = 64 / block 64 / 8-bit
+    // kernel, x 4 workgroups of the others).  A wavefront that has its SIMD to itself runs no faster than one that shares
+    // it, so when the last group of an XCD runs out of row blocks the launch drains for as long as the last-started
+    // rows take.  With several groups per XCD the lightest rows of the whole range - half as many as the XCD holds
+    // workgroups - are therefore kept back and started last, heaviest first: they are the shortest filler there is,
+    // and being few and short they cost the L2 little.
+    const int64_t resident = (s->d == 64 && s->block == 64 && bits_qk == 8) ? 256 : 128;
+    auto live = [&](int32_t id) {
+        const int64_t h = (id / k) % s->nh, i = id % k;
+        return h_row_ptr[h * (k + 1) + i + 1] - h_row_ptr[h * (k + 1) + i];
+    };
+    auto heavier = [&](int32_t a, int32_t b) { return live(a) > live(b); };
+    std::vector<int32_t> ids, kept_back;
+    std::vector<char> held;
     for (int x = 0; x < 8; ++x) {
         const int64_t lo = x * per_xcd, hi = std::min(total, (x + 1) * per_xcd);
-        const bool one_group = lo < hi && ((hi - 1) / k - lo / k + 1) * kv_bytes <= l2_budget;
-        int64_t pos = lo;
+        if (lo >= hi) continue;
+        const bool one_group = ((hi - 1) / k - lo / k + 1) * kv_bytes <= l2_budget;
+        const bool several_groups = !one_group && ((hi - 1) / k) / window != (lo / k) / window;
+        held.assign(hi - lo, 0);
+        kept_back.clear();
+        if (several_groups) {
+            ids.resize(hi - lo);
+            for (int64_t t = lo; t < hi; ++t) ids[t - lo] = (int32_t)t;
+            std::stable_sort(ids.begin(), ids.end(), [&](int32_t a, int32_t b) { return live(a) < live(b); });
+            kept_back.assign(ids.begin(), ids.begin() + std::min<int64_t>(resident / 2, (hi - lo) / 4));
+            for (int32_t id : kept_back) held[id - lo] = 1;
+            std::stable_sort(kept_back.begin(), kept_back.end(), heavier);
+        }
+        int64_t pos = lo, out = lo;
         while (pos < hi) {
             const int64_t group = (pos / k) / window;
             int64_t end = pos;
             while (end < hi && (one_group || (end / k) / window == group)) ++end;
-            ids.resize(end - pos);
-            for (int64_t t = pos; t < end; ++t) ids[t - pos] = (int32_t)t;
-            auto live = [&](int32_t id) {
-                const int64_t h = (id / k) % s->nh, i = id % k;
-                return h_row_ptr[h * (k + 1) + i + 1] - h_row_ptr[h * (k + 1) + i];
-            };
-            std::stable_sort(ids.begin(), ids.end(), [&](int32_t a, int32_t b) { return live(a) > live(b); });
-            for (int64_t t = pos; t < end; ++t) h_order[t] = ids[t - pos];
+            ids.clear();
+            for (int64_t t = pos; t < end; ++t)
+                if (!held[t - lo]) ids.push_back((int32_t)t);
+            std::stable_sort(ids.begin(), ids.end(), heavier);
+            for (int32_t id : ids) h_order[out++] = id;
             pos = end;
         }
+        for (int32_t id : kept_back) h_order[out++] = id;
     }
     return PARO_OK;
 }

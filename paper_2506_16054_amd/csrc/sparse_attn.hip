@@ -47,6 +47,28 @@ namespace paro {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
+// Measurement build only (lib/libparo_timeline.so, read by `python -m paper_2506_16054_amd.probe --timeline`; the
+// product library is compiled without it): every wavefront of the two main integer kernels records the constant-rate
+// clock when it starts and when it has stored its rows, and the number of column blocks it visited, at slot
+// (launch item) x (wavefronts per workgroup) + wavefront.  paro_timeline_read copies the records to the host.
+#ifndef PARO_TIMELINE
+#define PARO_TIMELINE 0
+#endif
+#if PARO_TIMELINE
+constexpr int kTimelineSlots = 1 << 16;
+__device__ long long timeline_records[kTimelineSlots][3];
+#define PARO_TIMELINE_BEGIN const long long timeline_start = wall_clock64();
+#define PARO_TIMELINE_END(slot, lane, blocks)                  \
+    if ((lane) == 0 && (slot) < kTimelineSlots) {              \
+        timeline_records[slot][0] = timeline_start;            \
+        timeline_records[slot][1] = wall_clock64();            \
+        timeline_records[slot][2] = (blocks);                  \
+    }
+#else
+#define PARO_TIMELINE_BEGIN
+#define PARO_TIMELINE_END(slot, lane, blocks)
+#endif
+
 struct AttnArgs {
     const uint8_t* q;
     const uint8_t* k;
@@ -641,6 +663,7 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
     const int lane = threadIdx.x;
     const int n = lane & 31;
     const int g = lane >> 5;
+    PARO_TIMELINE_BEGIN
 
     const int* rp = a.row_ptr + (size_t)h * (a.kblocks + 1) + i;
     const int beg = __builtin_amdgcn_readfirstlane(min(max(rp[0], 0), a.nnz));
@@ -971,6 +994,7 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
                            acc[H][dt][4 * qd + 3] * inv);
         }
     }
+    PARO_TIMELINE_END(item, lane, cnt)
 }
 
 // -------------------------------------------------------------------------------------------
@@ -1041,6 +1065,7 @@ __global__ __launch_bounds__(256, 3) void attn_i8_q16_kernel(AttnArgs a) {
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 15;
     const int G = lane >> 4;
+    PARO_TIMELINE_BEGIN
 
     const int* rp = a.row_ptr + (size_t)h * (a.kblocks + 1) + i;
     const int beg = __builtin_amdgcn_readfirstlane(min(max(rp[0], 0), a.nnz));
@@ -1263,6 +1288,7 @@ __global__ __launch_bounds__(256, 3) void attn_i8_q16_kernel(AttnArgs a) {
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) store4(orow + 16 * ct, acc[ct][0] * inv, acc[ct][1] * inv, acc[ct][2] * inv, acc[ct][3] * inv);
     }
+    PARO_TIMELINE_END(4 * item + w, lane, cnt)
 }
 
 // -------------------------------------------------------------------------------------------
@@ -1924,3 +1950,15 @@ extern "C" int paro_sparse_attn_unpermuted_rawq(const paro_shape* s, paro_dtype 
     return paro::attn_entry("paro_sparse_attn_unpermuted_rawq", s, 8, bits_pv, q, nullptr, k, sk, v, sv, row_ptr, col_idx, nnz, row_order,
                             h_perm_ids, out_dtype, o, stream, q_dtype == PARO_BF16 ? 1 : 2);
 }
+
+#if PARO_TIMELINE
+// h_records: int64 [slots][3] (HOST; start clock, end clock, column blocks visited); returns the clock rate in kHz (> 0)
+// or a negative status.  Synchronises the device.
+extern "C" int64_t paro_timeline_read(int64_t* h_records, int64_t slots) {
+    if (!h_records || slots < 0 || slots > paro::kTimelineSlots) return PARO_EINVAL;
+    if (hipMemcpyFromSymbol(h_records, HIP_SYMBOL(paro::timeline_records), sizeof(long long) * 3 * (size_t)slots) != hipSuccess) return PARO_EHIP;
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess) return PARO_EHIP;
+    return khz;
+}
+#endif

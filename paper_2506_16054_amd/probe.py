@@ -3,7 +3,11 @@ rate the GPU sustains, the issue cost of single vector-ALU instructions, and a r
 of one live block of the INT8 attention kernel.  Not part of the product library; nothing under
 ``binding`` or ``pipeline`` loads it.
 
-    python -m paper_2506_16054_amd.probe          # prints the issue-cost table as markdown
+    python -m paper_2506_16054_amd.probe                      # prints the issue-cost table as markdown
+    python -m paper_2506_16054_amd.probe --timeline flux [records.npy]   # when the wavefronts of one attention launch start and end
+
+The second form loads lib/libparo_timeline.so (the product sources with sparse_attn.hip compiled under
+-DPARO_TIMELINE=1) in place of the product library, in this process only.
 """
 from __future__ import annotations
 
@@ -216,7 +220,91 @@ def markdown(tab: dict) -> str:
     return "\n".join(out)
 
 
+def timeline(workload: str, step_us: float | None = None, records_path: str | None = None) -> str:
+    """Markdown summary of one attention launch of the named workload: per class of row block (few / many column
+    blocks) when its wavefronts start and end and what a block costs them, and how many wavefronts are resident over time."""
+    import numpy as np
+    import torch
+
+    from . import binding as pb
+    from . import workloads as wl
+    from .pipeline import ParoAttention
+
+    if pb._lib is not None:
+        raise RuntimeError("the product library is already loaded in this process")
+    pb.LIBPATH = os.path.join(os.path.dirname(LIBPATH), "libparo_timeline.so")
+    w = wl.WORKLOADS[workload]
+    s = pb.shape_of(w)
+    perm_ids = wl.make_perm_ids(w)
+    bitmask = wl.pack_bitmask(wl.make_block_masks(w, lambda pid: pb.paro_perm_index(s, pid), perm_ids))
+    dev = torch.device("cuda:0")
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    q = torch.empty((w.B, w.nh, w.N, w.d), dtype=tdt, device=dev)
+    k, v = torch.empty_like(q), torch.empty_like(q)
+    for h in range(w.nh):
+        for dst, src in zip((q, k, v), wl.make_head_qkv(w, 0, h)):
+            dst[0, h] = torch.from_numpy(src).to(dev)
+    pa = ParoAttention(s, perm_ids, bitmask, w.bits_qk, w.bits_pv, tdt, dev)
+    pa.prepare_fused_qkv(q, k, v)  # the launches bench.py times
+    for _ in range(60):
+        pa.attend_fused()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    pa.attend_fused()
+    e1.record()
+    torch.cuda.synchronize()
+    waves_per_wg = 4 if (w.d == 128 and w.bits_qk == 8 and w.bits_pv == 8) else 1
+    if not (w.block == 64 and w.bits_qk == 8 and (waves_per_wg == 4 or w.d == 64)):
+        raise RuntimeError("only the one-wavefront (d = 64) and the four-wavefront (d = 128, 8-bit) kernels record a timeline")
+    slots = waves_per_wg * w.B * w.nh * w.k
+    rec = np.zeros((slots, 3), dtype=np.int64)
+    read = pb.lib().paro_timeline_read
+    read.restype = ctypes.c_int64
+    khz = read(ctypes.c_void_p(rec.ctypes.data), ctypes.c_int64(slots))
+    if khz <= 0:
+        raise RuntimeError("paro_timeline_read: %d" % khz)
+    if records_path:
+        np.save(records_path, rec)  # [slot][start clock, end clock, column blocks]; slot = row block x wavefronts per block + wavefront
+    t0 = rec[:, 0].min()
+    start, end, cnt = (rec[:, 0] - t0) * 1e3 / khz, (rec[:, 1] - t0) * 1e3 / khz, rec[:, 2]
+    heavy = 2 * cnt > w.k
+    out = ["workload %s: %d wavefronts (%d per row block), launch %.1f us by HIP events, %.1f us from the first start to the last end"
+           % (workload, slots, waves_per_wg, 1e3 * e0.elapsed_time(e1), end.max()), "",
+           "| row blocks | wavefronts | column blocks | start us (min / median / max) | end us (min / median / max) | us per block (median) |",
+           "|---|---|---|---|---|---|"]
+    for label, sel in (("more than half of all column blocks live", heavy), ("the others", ~heavy)):
+        if sel.any():
+            per = ((end - start) / np.maximum(cnt, 1))[sel]
+            out.append("| %s | %d | %d ... %d | %.1f / %.1f / %.1f | %.1f / %.1f / %.1f | %.2f |" % (
+                label, sel.sum(), cnt[sel].min(), cnt[sel].max(), start[sel].min(), np.median(start[sel]), start[sel].max(),
+                end[sel].min(), np.median(end[sel]), end[sel].max(), np.median(per)))
+    # the kernels give launch positions [x * per_xcd, (x + 1) * per_xcd) to XCD x; row_order maps positions to row blocks
+    total = w.B * w.nh * w.k
+    per_xcd = (total + 7) // 8
+    order = pa.row_order.cpu().numpy() if pa.row_order is not None else np.arange(total)
+    xcd_of_item = np.empty(total, dtype=np.int64)
+    xcd_of_item[order] = np.arange(total) // per_xcd
+    xcd = np.repeat(xcd_of_item, waves_per_wg)
+    out += ["", "| XCD | row blocks | column blocks visited | last start us | last end us | median end us of its last 5 % of wavefronts to end |", "|---|---|---|---|---|---|"]
+    for x in range(8):
+        sel = xcd == x
+        if sel.any():
+            ends = np.sort(end[sel])
+            out.append("| %d | %d | %d | %.1f | %.1f | %.1f |" % (x, sel.sum() // waves_per_wg, cnt[sel].sum() // waves_per_wg, start[sel].max(), ends[-1],
+                                                                np.median(ends[-max(1, len(ends) // 20):])))
+    out += ["", "| at us | wavefronts resident | of them: many-block rows | wavefronts started so far |", "|---|---|---|---|"]
+    if step_us is None:  # about forty rows
+        step_us = max(5.0, 5.0 * round(end.max() / 200.0))
+    for t in np.arange(0.0, end.max() + step_us, step_us):
+        run = (start <= t) & (end > t)
+        out.append("| %.0f | %d | %d | %d |" % (t, run.sum(), (run & heavy).sum(), (start <= t).sum()))
+    return "\n".join(out)
+
+
 if __name__ == "__main__":
+    if len(sys.argv) > 1 and sys.argv[1] == "--timeline":
+        sys.stdout.write(timeline(sys.argv[2] if len(sys.argv) > 2 else "flux", records_path=sys.argv[3] if len(sys.argv) > 3 else None) + "\n")
+        sys.exit(0)
     sys.stdout.write(markdown(issue_table()) + "\n")
     sys.stdout.write("\n| plain streaming copy, 512 MB read | TB/s (read + written) |\n|---|---|\n")
     sys.stdout.write("| one byte written per byte read | %.2f |\n| one byte written per two read (the quantizer's mix) | %.2f |\n"

@@ -202,9 +202,21 @@ def test_k_smoothing_entry_points_validate_on_the_host():
     assert sm(9, 8, ok.ctypes.data, fake, fake, other, fake) == pb.PARO_EINVAL
 
 
-def test_row_schedule_is_a_permutation_heaviest_first_within_l2_groups():
+def _check_grouped_range(chunk, lv, groups, tail):
+    """One XCD's range with several L2 groups: the last `tail` positions hold the lightest row blocks of the whole
+    range, heaviest first; in front of them the groups follow each other, each heaviest first."""
+    main, back = slice(0, len(chunk) - tail), slice(len(chunk) - tail, None)
+    assert lv[back].max() <= lv[main].min()  # nothing lighter was left in the groups
+    assert np.all(np.diff(lv[back]) <= 0)
+    assert np.all(np.diff(groups[main]) >= 0)
+    for gidx in np.unique(groups[main]):
+        assert np.all(np.diff(lv[main][groups[main] == gidx]) <= 0)
+
+
+def test_row_schedule_is_a_permutation_heaviest_first_within_l2_groups_lightest_rows_last():
     rng = np.random.default_rng(5)
-    # headline shape: one head's K+V (2.25 MB) fills the L2 budget alone -> groups of one head
+    # headline shape: one head's K+V (2.25 MB) fills the L2 budget alone -> groups of one head; the kernel of this
+    # shape keeps 256 workgroups on an XCD, so the 128 lightest row blocks of each XCD's range start last
     s = pb.make_shape(1, 48, 64, 13, 30, 45, 0, 64)
     k = 275
     live = rng.integers(1, 120, size=(48, k))
@@ -218,11 +230,7 @@ def test_row_schedule_is_a_permutation_heaviest_first_within_l2_groups():
     for x in range(8):
         chunk = order[x * per_xcd:(x + 1) * per_xcd]
         assert np.array_equal(np.sort(chunk), np.arange(x * per_xcd, min(total, (x + 1) * per_xcd)))  # XCD ranges are kept
-        heads = chunk // k
-        assert np.all(np.diff(heads) >= 0)  # heads stay in order: one head per L2 group
-        for h in np.unique(heads):
-            lv = live[h, chunk[heads == h] % k]
-            assert np.all(np.diff(lv) <= 0)  # heaviest first
+        _check_grouped_range(chunk, live[chunk // k, chunk % k], chunk // k, 128)
     # Flux shape: 1.18 MB per head; an XCD's whole range (three heads, 3.5 MB) fits the L2, so it
     # is sorted as one group and every long row starts first
     s2 = pb.make_shape(1, 24, 128, 1, 64, 64, 512, 64)
@@ -236,8 +244,7 @@ def test_row_schedule_is_a_permutation_heaviest_first_within_l2_groups():
         chunk = order2[x * 3 * k2:(x + 1) * 3 * k2]
         assert set(chunk // k2) == {3 * x, 3 * x + 1, 3 * x + 2}
         assert np.all(np.diff(live2[chunk // k2, chunk % k2]) <= 0)
-    # 20 heads of the same size: XCD ranges of 2.5 heads touch 3 or 4 heads; those touching 3 are
-    # one group, the others fall back to head-aligned groups of three heads
+    # 20 heads of the same size: XCD ranges of 2.5 heads touch 3 heads each and are one group
     s3 = pb.make_shape(1, 20, 128, 1, 64, 64, 512, 64)
     live3 = rng.integers(1, 73, size=(20, k2))
     rp3 = np.zeros((20, k2 + 1), np.int32)
@@ -249,14 +256,24 @@ def test_row_schedule_is_a_permutation_heaviest_first_within_l2_groups():
         lo, hi = x * per3, (x + 1) * per3
         chunk = order3[lo:hi]
         assert np.array_equal(np.sort(chunk), np.arange(lo, hi))
-        lv = live3[chunk // k2, chunk % k2]
-        if (hi - 1) // k2 - lo // k2 + 1 <= 3:
-            assert np.all(np.diff(lv) <= 0)
-        else:
-            groups = (chunk // k2) // 3
-            assert np.all(np.diff(groups) >= 0)
-            for gidx in np.unique(groups):
-                assert np.all(np.diff(lv[groups == gidx]) <= 0)
+        assert np.all(np.diff(live3[chunk // k2, chunk % k2]) <= 0)
+    # a long d = 128 layer: 4.5 MB of K+V per head, one head per group, three heads per XCD; the kernels of this shape
+    # keep 128 workgroups on an XCD -> 64 row blocks kept back; 4-bit codes (2.25 MB per head) and bf16 (9 MB) also give
+    # groups of one head
+    s4 = pb.make_shape(1, 24, 128, 13, 30, 45, 0, 64)
+    live4 = rng.integers(1, 200, size=(24, k))
+    rp4 = np.zeros((24, k + 1), np.int32)
+    rp4[:, 1:] = np.cumsum(live4, axis=1)
+    for bits, heads_per_group in ((8, 1), (4, 1), (16, 1)):
+        order4 = pb.paro_schedule_rows(s4, bits, bits, rp4)
+        assert np.array_equal(np.sort(order4), np.arange(24 * k))
+        for x in range(8):
+            chunk = order4[x * 3 * k:(x + 1) * 3 * k]
+            assert np.array_equal(np.sort(chunk), np.arange(x * 3 * k, (x + 1) * 3 * k))
+            _check_grouped_range(chunk, live4[chunk // k, chunk % k], (chunk // k) // heads_per_group, 64)
+    # a two-row-block problem: ranges of one row block, nothing to keep back
+    s5 = pb.make_shape(1, 2, 64, 1, 8, 16, 0, 64)
+    assert np.array_equal(pb.paro_schedule_rows(s5, 8, 8, np.array([[0, 1, 3], [3, 5, 6]], np.int32)), np.arange(4))
     with pytest.raises(pb.ParoError):
         pb.paro_schedule_rows(s2, 5, 8, rp2)
 
