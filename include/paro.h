@@ -128,6 +128,10 @@ int paro_check_row_order(const paro_shape* s, const int32_t* h_order);
  * one group.  A range of several groups keeps its lightest row blocks (half as many as the XCD
  * holds workgroups, at most a quarter of the range) out of the groups and starts them last, heaviest
  * first: the launch ends when the last-started row blocks are done, and these are the shortest.
+ * When every XCD's range is a whole number of (batch, head) pairs and the heads differ in live
+ * blocks (one threshold per head, Sec. 4.2 (3)) so that the natural order would load some XCD more
+ * than 2 % above the mean, whole heads are dealt to the ranges heaviest first, each to the range
+ * with the least work that still has room; heads of equal work stay in their natural ranges.
  * bits_* size the footprint and, with d and block, name the kernel.  Host only. */
 int paro_schedule_rows(const paro_shape* s, int bits_qk, int bits_pv, const int32_t* h_row_ptr,
                        int32_t* h_order);

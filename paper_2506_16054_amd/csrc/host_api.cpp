@@ -223,8 +223,47 @@ int paro_schedule_rows(const paro_shape* s, int bits_qk, int bits_pv, const int3
     // workgroups - are therefore kept back and started last, heaviest first: they are the shortest filler there is,
     // and being few and short they cost the L2 little.
     const int64_t resident = (s->d == 64 && s->block == 64 && bits_qk == 8) ? 256 : 128;
+    // Which (batch, head) an XCD works on.  Positions are in units of whole (batch, head) "slots" of k row blocks; slot
+    // v holds head_at[v].  Masks made with one threshold per head (Sec. 4.2 (3)) can differ in live blocks from head to
+    // head; when every XCD's range is a whole number of heads and the heads in their natural order would load some XCD
+    // more than 2 % above the mean, heads are dealt heaviest first to the XCD with the least work that still has room.
+    const int64_t n_heads = (int64_t)s->B * s->nh;
+    std::vector<int64_t> head_at(n_heads);
+    for (int64_t v = 0; v < n_heads; ++v) head_at[v] = v;
+    if (per_xcd % k == 0 && total == 8 * per_xcd) {
+        const int64_t hpx = per_xcd / k;
+        std::vector<int64_t> work(n_heads), load(8, 0);
+        int64_t sum = 0;
+        for (int64_t v = 0; v < n_heads; ++v) {
+            const int64_t h = v % s->nh;
+            work[v] = (int64_t)h_row_ptr[h * (k + 1) + k] - h_row_ptr[h * (k + 1)];
+            load[v / hpx] += work[v];
+            sum += work[v];
+        }
+        if (*std::max_element(load.begin(), load.end()) * 8 * 100 > sum * 102) {
+            std::vector<int64_t> by_work(n_heads);
+            for (int64_t v = 0; v < n_heads; ++v) by_work[v] = v;
+            std::stable_sort(by_work.begin(), by_work.end(), [&](int64_t a, int64_t b) { return work[a] > work[b]; });
+            std::vector<std::vector<int64_t>> dealt(8);
+            std::fill(load.begin(), load.end(), 0);
+            for (int64_t v : by_work) {
+                int best = -1;
+                for (int x = 0; x < 8; ++x)
+                    if ((int64_t)dealt[x].size() < hpx && (best < 0 || load[x] < load[best])) best = x;
+                dealt[best].push_back(v);
+                load[best] += work[v];
+            }
+            int64_t v = 0;
+            for (int x = 0; x < 8; ++x) {
+                std::sort(dealt[x].begin(), dealt[x].end());
+                for (int64_t hd : dealt[x]) head_at[v++] = hd;
+            }
+        }
+    }
+    // ids below are positions in slot order: id -> row block head_at[id / k] * k + id % k
+    auto item = [&](int32_t id) { return (int32_t)(head_at[id / k] * k + id % k); };
     auto live = [&](int32_t id) {
-        const int64_t h = (id / k) % s->nh, i = id % k;
+        const int64_t h = head_at[id / k] % s->nh, i = id % k;
         return h_row_ptr[h * (k + 1) + i + 1] - h_row_ptr[h * (k + 1) + i];
     };
     auto heavier = [&](int32_t a, int32_t b) { return live(a) > live(b); };
@@ -254,10 +293,10 @@ int paro_schedule_rows(const paro_shape* s, int bits_qk, int bits_pv, const int3
             for (int64_t t = pos; t < end; ++t)
                 if (!held[t - lo]) ids.push_back((int32_t)t);
             std::stable_sort(ids.begin(), ids.end(), heavier);
-            for (int32_t id : ids) h_order[out++] = id;
+            for (int32_t id : ids) h_order[out++] = item(id);
             pos = end;
         }
-        for (int32_t id : kept_back) h_order[out++] = id;
+        for (int32_t id : kept_back) h_order[out++] = item(id);
     }
     return PARO_OK;
 }

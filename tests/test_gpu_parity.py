@@ -495,3 +495,36 @@ def test_row_schedule_does_not_change_results(name):
     torch.cuda.synchronize()
     assert torch.equal(pa.op, ref)
     assert not np.array_equal(pa.h_row_order, np.arange(pa.h_row_order.size))
+
+
+def test_heads_of_unequal_density_are_dealt_to_the_xcds_and_results_do_not_change():
+    """Masks whose density differs from head to head (one threshold per head, Sec. 4.2 (3)): the launch order moves
+    whole heads between the XCDs' ranges; the output is bit-identical to the natural order and matches the oracle."""
+    torch, pb = _torch(), _pb()
+    from paper_2506_16054_amd.pipeline import ParoAttention
+
+    w = wl.Workload("uneq", 1, 16, 64, 2, 8, 12, 0, 32, 0.25, 8, 8, "bf16", 77, perm_choice=(0, 2, 5))
+    dense = w.replace(density=0.9)
+    perm_ids = wl.make_perm_ids(w)
+    masks = wl.make_block_masks(w, gather_fn(w), perm_ids)
+    masks[:8] = wl.make_block_masks(dense, gather_fn(w), perm_ids)[:8]  # heads 0..7 dense, 8..15 sparse
+    bits, row_ptr, col_idx = blocklist_for(w, masks)
+    s = pb.shape_of(w)
+    pa = ParoAttention(s, perm_ids, bits, w.bits_qk, w.bits_pv, tdtype(w.dtype))
+    order = pa.h_row_order
+    pb.paro_check_row_order(s, order)
+    live = masks.sum(2)
+    loads = np.array([live[c // w.k, c % w.k].sum() for c in np.split(order, 8)])
+    natural = np.array([live[2 * x:2 * x + 2].sum() for x in range(8)])
+    assert natural.max() > 1.3 * natural.mean() and loads.max() < 1.1 * loads.mean()
+    q, k, v = wl.make_qkv(w)
+    o = pa.run(*(to_dev(x, w.dtype) for x in (q, k, v))).clone()
+    torch.cuda.synchronize()
+    pa.op.fill_(float("nan"))
+    pb.paro_sparse_attn(pa.s, pa.bits_qk, pa.bits_pv, pa.qc, pa.sq, pa.kc, pa.sk, pa.vc, pa.sv, pa.row_ptr, pa.col_idx, pa.op, None)
+    torch.cuda.synchronize()
+    assert torch.equal(pa.finish(), o)
+    got = host(o)
+    for h in (0, 7, 8, 15):
+        ref = oracle_head(w, q[0, h], k[0, h], v[0, h], perm_ids[h], row_ptr[h], col_idx)
+        check_attention(got[0, h], ref["o"], po.unpermute(ref["flip_risk"], ref["idx"]), MAX_ABS, REL_L2, "unequal heads, head %d" % h)
