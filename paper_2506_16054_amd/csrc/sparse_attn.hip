@@ -56,16 +56,28 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 #endif
 #if PARO_TIMELINE
 constexpr int kTimelineSlots = 1 << 16;
-__device__ long long timeline_records[kTimelineSlots][3];
-#define PARO_TIMELINE_BEGIN const long long timeline_start = wall_clock64();
-#define PARO_TIMELINE_END(slot, lane, blocks)                  \
-    if ((lane) == 0 && (slot) < kTimelineSlots) {              \
-        timeline_records[slot][0] = timeline_start;            \
-        timeline_records[slot][1] = wall_clock64();            \
-        timeline_records[slot][2] = (blocks);                  \
+constexpr int kTimelineFields = 8;  // start, end (constant-rate clock), column blocks, shader cycles of phases 0..4
+__device__ long long timeline_records[kTimelineSlots][kTimelineFields];
+#define PARO_TIMELINE_BEGIN                                \
+    const long long timeline_start = wall_clock64();       \
+    long long timeline_last = clock64(), timeline_phase[5] = {0, 0, 0, 0, 0};
+// closes phase i of the block loop (shader clock at issue, not at completion, of the instructions in front of it)
+#define PARO_TIMELINE_PHASE(i)                             \
+    {                                                      \
+        const long long now_ = clock64();                  \
+        timeline_phase[i] += now_ - timeline_last;         \
+        timeline_last = now_;                              \
+    }
+#define PARO_TIMELINE_END(slot, lane, blocks)                                         \
+    if ((lane) == 0 && (slot) < kTimelineSlots) {                                     \
+        timeline_records[slot][0] = timeline_start;                                   \
+        timeline_records[slot][1] = wall_clock64();                                   \
+        timeline_records[slot][2] = (blocks);                                         \
+        for (int f_ = 0; f_ < 5; ++f_) timeline_records[slot][3 + f_] = timeline_phase[f_]; \
     }
 #else
 #define PARO_TIMELINE_BEGIN
+#define PARO_TIMELINE_PHASE(i)
 #define PARO_TIMELINE_END(slot, lane, blocks)
 #endif
 
@@ -1163,6 +1175,7 @@ __global__ __launch_bounds__(256, 3) void attn_i8_q16_kernel(AttnArgs a) {
         const float sv_now = sv0;
         const uint8_t* kslot = &kring[t & 1][0];
         const uint8_t* vslot = &vring[t & 1][0];
+        PARO_TIMELINE_PHASE(3)  // behind the previous block's accumulator update (and the loop's own overhead)
 
         // ---- S^T = K_j Q_i^T (i32, biased): four 16-key tiles
         v4acc sacc[4];
@@ -1197,8 +1210,10 @@ __global__ __launch_bounds__(256, 3) void attn_i8_q16_kernel(AttnArgs a) {
         if (lane == 0) tile_e[t & 1][w] = eb;
         // ---- everything this wavefront has in flight (its share of K_{t+1} and V_t) has landed; behind the
         // barrier both tiles and all four exponents are whole, K_t has been read by all and V_{t-1} is consumed
+        PARO_TIMELINE_PHASE(0)  // K reads, products, row maximum, share of the tile exponent
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
+        PARO_TIMELINE_PHASE(1)  // wait for the tiles and for the other wavefronts
         if (t + 2 < cnt) request_k(j2, t & 1);
         const int j_v = j1;
         const float e = __uint_as_float(min(min(tile_e[t & 1][0], tile_e[t & 1][1]), min(tile_e[t & 1][2], tile_e[t & 1][3])));
@@ -1253,6 +1268,7 @@ __global__ __launch_bounds__(256, 3) void attn_i8_q16_kernel(AttnArgs a) {
             pf[T] = (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u);
         }
         l = fmaf(rs, w_blk, l);
+        PARO_TIMELINE_PHASE(2)  // exponentials, row sum, codes
         // ---- O^T += (sP sv_j 2^(m' - m_ref)) V_j^T P^T: eight 16-channel tiles, one instruction each
         const float sv_eff = w_blk * sv_now;
 #pragma unroll
@@ -1274,11 +1290,13 @@ __global__ __launch_bounds__(256, 3) void attn_i8_q16_kernel(AttnArgs a) {
         for (int off = 32; off >= 1; off >>= 1) sk_max = fmaxf(sk_max, __shfl_xor(sk_max, off));
         fold = sq_i * sk_max * kAccBiasF < 8192.0f;
     }
+    PARO_TIMELINE_PHASE(4)  // everything in front of the block loop
     if (fold) {
         for (int t = 0; t < cnt; ++t) step(std::bool_constant<FOLDABLE>{}, t);
     } else {
         for (int t = 0; t < cnt; ++t) step(std::false_type{}, t);
     }
+    PARO_TIMELINE_PHASE(3)
 
     const float l_tot = quad_rows_sum(l) * 65535.0f;
     const float inv = (row_valid && l_tot > 0.0f) ? 1.0f / l_tot : 0.0f;
@@ -1952,11 +1970,12 @@ extern "C" int paro_sparse_attn_unpermuted_rawq(const paro_shape* s, paro_dtype 
 }
 
 #if PARO_TIMELINE
-// h_records: int64 [slots][3] (HOST; start clock, end clock, column blocks visited); returns the clock rate in kHz (> 0)
+// h_records: int64 [slots][8] (HOST; start clock, end clock, column blocks visited, shader cycles of the block loop's
+// phases 0..3 and of the part in front of the loop); returns the rate of the start/end clock in kHz (> 0)
 // or a negative status.  Synchronises the device.
 extern "C" int64_t paro_timeline_read(int64_t* h_records, int64_t slots) {
     if (!h_records || slots < 0 || slots > paro::kTimelineSlots) return PARO_EINVAL;
-    if (hipMemcpyFromSymbol(h_records, HIP_SYMBOL(paro::timeline_records), sizeof(long long) * 3 * (size_t)slots) != hipSuccess) return PARO_EHIP;
+    if (hipMemcpyFromSymbol(h_records, HIP_SYMBOL(paro::timeline_records), sizeof(long long) * paro::kTimelineFields * (size_t)slots) != hipSuccess) return PARO_EHIP;
     int dev = 0, khz = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess) return PARO_EHIP;
     return khz;

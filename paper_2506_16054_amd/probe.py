@@ -257,14 +257,16 @@ def timeline(workload: str, step_us: float | None = None, records_path: str | No
     if not (w.block == 64 and w.bits_qk == 8 and (waves_per_wg == 4 or w.d == 64)):
         raise RuntimeError("only the one-wavefront (d = 64) and the four-wavefront (d = 128, 8-bit) kernels record a timeline")
     slots = waves_per_wg * w.B * w.nh * w.k
-    rec = np.zeros((slots, 3), dtype=np.int64)
+    rec = np.zeros((slots, 8), dtype=np.int64)
     read = pb.lib().paro_timeline_read
     read.restype = ctypes.c_int64
     khz = read(ctypes.c_void_p(rec.ctypes.data), ctypes.c_int64(slots))
     if khz <= 0:
         raise RuntimeError("paro_timeline_read: %d" % khz)
     if records_path:
-        np.save(records_path, rec)  # [slot][start clock, end clock, column blocks]; slot = row block x wavefronts per block + wavefront
+        # [slot][start clock, end clock, column blocks, shader cycles of phases 0..3 of the block loop, of the part in front of
+        # it]; slot = row block x wavefronts per block + wavefront
+        np.save(records_path, rec)
     t0 = rec[:, 0].min()
     start, end, cnt = (rec[:, 0] - t0) * 1e3 / khz, (rec[:, 1] - t0) * 1e3 / khz, rec[:, 2]
     heavy = 2 * cnt > w.k
@@ -278,6 +280,16 @@ def timeline(workload: str, step_us: float | None = None, records_path: str | No
             out.append("| %s | %d | %d ... %d | %.1f / %.1f / %.1f | %.1f / %.1f / %.1f | %.2f |" % (
                 label, sel.sum(), cnt[sel].min(), cnt[sel].max(), start[sel].min(), np.median(start[sel]), start[sel].max(),
                 end[sel].min(), np.median(end[sel]), end[sel].max(), np.median(per)))
+    if waves_per_wg == 4:  # the four-wavefront kernel also records where a block's cycles go
+        names = ("K reads, QK^T products, row maximum, share of the tile exponent", "wait for the tiles and the other wavefronts (barrier)",
+                 "exponentials, row sum, codes", "PV products, accumulator update, next requests")
+        out += ["", "| shader cycles per block (median over the wavefronts) | " + " | ".join(names) + " | sum | in front of the loop (per wavefront) |",
+                "|---|---|---|---|---|---|---|"]
+        for label, sel in (("more than half of all column blocks live", heavy), ("the others, started in the first 5 us", ~heavy & (start < 5.0)),
+                           ("the others, started later", ~heavy & (start >= 5.0))):
+            if sel.any():
+                per = rec[sel, 3:7] / np.maximum(cnt[sel], 1)[:, None]
+                out.append("| %s | %s | %.0f | %.0f |" % (label, " | ".join("%.0f" % x for x in np.median(per, axis=0)), np.median(per.sum(1)), np.median(rec[sel, 7])))
     # the kernels give launch positions [x * per_xcd, (x + 1) * per_xcd) to XCD x; row_order maps positions to row blocks
     total = w.B * w.nh * w.k
     per_xcd = (total + 7) // 8
