@@ -97,6 +97,25 @@ def test_probe_library_exports_what_bench_calls():
     assert lib.paro_probe_issue_kinds() >= 22
 
 
+def test_timeline_library_is_the_product_plus_the_record_reader_and_the_product_has_no_recorder():
+    """lib/libparo_timeline.so (read by `probe --timeline`) exports everything the product library does plus
+    paro_timeline_read; the product library itself carries no timeline code."""
+    import ctypes
+    import os
+
+    import torch  # noqa: F401
+
+    from paper_2506_16054_amd import binding as pb
+
+    timeline = os.path.join(os.path.dirname(pb.LIBPATH), "libparo_timeline.so")
+    assert os.path.exists(timeline), "build with python -m paper_2506_16054_amd.build"
+    tl = ctypes.CDLL(timeline)
+    for name in pb.EXPORTS:
+        assert hasattr(tl, name), name
+    assert hasattr(tl, "paro_timeline_read")
+    assert not hasattr(ctypes.CDLL(pb.LIBPATH), "paro_timeline_read")
+
+
 def test_bench_refuses_more_than_one_gpu():
     """The whole build runs on one GPU; the bench says so instead of timing anything (no GPU is touched)."""
     import os
