@@ -655,13 +655,18 @@ __device__ inline void lds_dma16(const uint8_t* base, unsigned lane_off, uint8_t
 // QSRC as in attn_i8_kernel: 0 = Q codes and scale from the quantizer; 1 (bf16) / 2 (fp32) = the unquantized Q in the
 // default token order, reordered and quantized here - the quantization group is the row block this wavefront owns,
 // so its absmax is one in-wave reduction.
-template <int PVBITS, typename OutT, int QSRC = 0>
-__global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
+// QKBITS 4: Q and K rows are 32 bytes of packed 4-bit codes; a lane fetches the 16 bytes that hold its 32 channels
+// (32 g .. 32 g + 31) of a K row - one fragment per key tile instead of two - and widens them to two 16-byte operands
+// (codes times 16, undone in the scale) right after the LDS read; Q is widened the same way once.
+template <int QKBITS, int PVBITS, typename OutT, int QSRC>
+__device__ __forceinline__ void attn_i8_w64_body(const AttnArgs& a) {
+    static_assert(QSRC == 0 || QKBITS == 8, "in-kernel quantization of Q produces 8-bit codes");
     constexpr int BLK = 64, D = 64;
+    constexpr int KPACK = QKBITS == 4 ? 2 : 1;
     constexpr int VPACK = PVBITS == 4 ? 2 : 1;
     constexpr float LOG2_QMAXP = PVBITS == 4 ? 2.807354922057604f : 6.988684686772166f;
     constexpr float kLog2_65535 = 15.999977986052736f;
-    // [slot][fragment][16 B per lane]; fragments 0-3: K (T,s); 4-7: V^T (dt,T) - with 4-bit V only 4-5: (dt), where
+    // [slot][fragment][16 B per lane]; fragments 0-3: K (T,s) - with 4-bit K only 0-1: (T); 4-7: V^T (dt,T) - with 4-bit V only 4-5: (dt), where
     // lane (n, g) holds bytes 16g .. 16g+15 of packed channel row 32 dt + n, i.e. the 32 slots of key tile g
     __shared__ __attribute__((aligned(16))) uint8_t ring[2][8][1024];
 
@@ -685,9 +690,9 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
     if (2 * cnt > a.kblocks) __builtin_amdgcn_s_setprio(2);
 
     const size_t head_rows = (size_t)bh * a.kblocks * BLK;
-    const uint8_t* kbase = a.k + head_rows * D;          // the head's K codes (wave-uniform)
+    const uint8_t* kbase = a.k + head_rows * D / KPACK;  // the head's K codes (wave-uniform)
     const uint8_t* vbase = a.v + head_rows * D / VPACK;  // the head's V^T codes (wave-uniform)
-    const unsigned klane = n * D + 16 * g;               // this lane's K fragment of key tile 0, step 0, inside a block
+    const unsigned klane = n * (D / KPACK) + 16 * g;     // this lane's K fragment of key tile 0, step 0, inside a block
     const unsigned vlane = n * (BLK / VPACK) + 16 * g;   // this lane's V^T piece of channel tile 0, inside a block
     const float* skp = a.sk + (size_t)bh * a.kblocks;
     const float* svp = a.sv + (size_t)bh * a.kblocks;
@@ -704,7 +709,11 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
         // unsigned number, than the pattern of every value a real row can have
         invalid_row[H] = row_valid[H] ? 0u : 0xFF800000u;
     }
-    if constexpr (QSRC == 0) {
+    if constexpr (QSRC == 0 && QKBITS == 4) {
+        sq_i = a.sq[(size_t)bh * a.kblocks + i] * a.qk_scale * (1.0f / 256.0f);  // Q and K codes both enter times 16
+#pragma unroll
+        for (int H = 0; H < 2; ++H) unpack_nibbles(*(const v4i*)(a.q + (head_rows + row[H]) * (D / 2) + 16 * g), qf[H][0], qf[H][1]);
+    } else if constexpr (QSRC == 0) {
         sq_i = a.sq[(size_t)bh * a.kblocks + i] * a.qk_scale;
 #pragma unroll
         for (int H = 0; H < 2; ++H) {
@@ -781,12 +790,17 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
 
     // request the tiles of column block j into ring slot `slot`
     auto request = [&](int j, int slot) {
-        const uint8_t* kp = kbase + (size_t)j * (BLK * D);  // j comes from a scalar register: kp, vp are wave-uniform
+        const uint8_t* kp = kbase + (size_t)j * (BLK * D / KPACK);  // j comes from a scalar register: kp, vp are wave-uniform
         const uint8_t* vp = vbase + (size_t)j * (BLK * D / VPACK);
-        lds_dma16<0>(kp, klane, &ring[slot][0][0]);
-        lds_dma16<32>(kp, klane, &ring[slot][1][0]);
-        lds_dma16<32 * D>(kp, klane, &ring[slot][2][0]);
-        lds_dma16<32 * D + 32>(kp, klane, &ring[slot][3][0]);
+        if constexpr (QKBITS == 4) {
+            lds_dma16<0>(kp, klane, &ring[slot][0][0]);
+            lds_dma16<32 * D / 2>(kp, klane, &ring[slot][1][0]);
+        } else {
+            lds_dma16<0>(kp, klane, &ring[slot][0][0]);
+            lds_dma16<32>(kp, klane, &ring[slot][1][0]);
+            lds_dma16<32 * D>(kp, klane, &ring[slot][2][0]);
+            lds_dma16<32 * D + 32>(kp, klane, &ring[slot][3][0]);
+        }
         if constexpr (PVBITS == 4) {
             lds_dma16<0>(vp, vlane, &ring[slot][4][0]);
             lds_dma16<32 * BLK / 2>(vp, vlane, &ring[slot][5][0]);
@@ -835,9 +849,14 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0); the other counters untouched
         v4i kf[2][2];
 #pragma unroll
-        for (int T = 0; T < 2; ++T)
+        for (int T = 0; T < 2; ++T) {
+            if constexpr (QKBITS == 4) {
+                unpack_nibbles(*(const v4i*)(slot + T * 1024), kf[T][0], kf[T][1]);
+            } else {
 #pragma unroll
-            for (int s = 0; s < 2; ++s) kf[T][s] = *(const v4i*)(slot + (2 * T + s) * 1024);
+                for (int s = 0; s < 2; ++s) kf[T][s] = *(const v4i*)(slot + (2 * T + s) * 1024);
+            }
+        }
         // ---- request the next block's tiles into the other slot (its previous content, block t-1, is consumed)
         if (t + 1 < cnt) {
             if (((t + 1) & 63) == 0) {
@@ -1007,6 +1026,17 @@ __global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
         }
     }
     PARO_TIMELINE_END(item, lane, cnt)
+}
+
+template <int PVBITS, typename OutT, int QSRC = 0>
+__global__ __launch_bounds__(64, 2) void attn_i8_w64_kernel(AttnArgs a) {
+    attn_i8_w64_body<8, PVBITS, OutT, QSRC>(a);
+}
+
+// the same wavefront program on 4-bit Q and K codes (Tab. 1, "QK (INT4)")
+template <int PVBITS, typename OutT>
+__global__ __launch_bounds__(64, 2) void attn_i8_w64_qk4_kernel(AttnArgs a) {
+    attn_i8_w64_body<4, PVBITS, OutT, 0>(a);
 }
 
 // -------------------------------------------------------------------------------------------
@@ -1849,11 +1879,16 @@ static void launch_rawq_shape(int d, int bits_pv, paro_dtype out_dtype, const At
 
 template <int QKBITS, int PVBITS>
 static void launch_i8(int blk, int d, paro_dtype out_dtype, const AttnArgs& a, hipStream_t st) {
-    if constexpr (PARO_ATTN_SINGLE_WAVE && QKBITS == 8) {
+    if constexpr (PARO_ATTN_SINGLE_WAVE) {
         if (blk == 64 && d == 64) {  // one wavefront per row block
             dim3 grid((unsigned)(a.per_xcd * 8));
-            if (out_dtype == PARO_F32) hipLaunchKernelGGL((attn_i8_w64_kernel<PVBITS, float>), grid, dim3(64), 0, st, a);
-            else hipLaunchKernelGGL((attn_i8_w64_kernel<PVBITS, uint16_t>), grid, dim3(64), 0, st, a);
+            if constexpr (QKBITS == 8) {
+                if (out_dtype == PARO_F32) hipLaunchKernelGGL((attn_i8_w64_kernel<PVBITS, float>), grid, dim3(64), 0, st, a);
+                else hipLaunchKernelGGL((attn_i8_w64_kernel<PVBITS, uint16_t>), grid, dim3(64), 0, st, a);
+            } else {
+                if (out_dtype == PARO_F32) hipLaunchKernelGGL((attn_i8_w64_qk4_kernel<PVBITS, float>), grid, dim3(64), 0, st, a);
+                else hipLaunchKernelGGL((attn_i8_w64_qk4_kernel<PVBITS, uint16_t>), grid, dim3(64), 0, st, a);
+            }
             return;
         }
     }

@@ -87,6 +87,7 @@ SMALL = {
 }
 # INT4 QK^T (the paper's all-INT4 setting) and the mixed INT4 QK / INT8 PV
 SMALL["video64_i4i4"] = wl.Workload("video64_i4i4", 1, 2, 64, 5, 12, 13, 0, 64, 0.4, 4, 4, "bf16", 20, perm_choice=(3, 0))
+SMALL["video64_i4i8_f32"] = wl.Workload("video64_i4i8_f32", 1, 2, 64, 5, 12, 13, 0, 64, 0.4, 4, 8, "f32", 23, perm_choice=(4, 1))
 SMALL["flux128_i4i8_f32"] = wl.Workload("flux128_i4i8_f32", 1, 2, 128, 1, 16, 16, 64, 64, 0.3, 4, 8, "f32", 21, perm_choice=(0, 5))
 SMALL["video32_i4i4_f32"] = wl.Workload("video32_i4i4_f32", 1, 2, 64, 3, 7, 9, 0, 32, 0.5, 4, 4, "f32", 22, perm_choice=(2, 5))
 REL_L2_BF16 = 5e-3  # stated bar of the unquantized mode
@@ -439,7 +440,7 @@ def test_empty_row_block_gives_zeros():
 
 
 @pytest.mark.parametrize("name", ["video64", "video64_int4", "video32_f32", "flux128", "flux128_b32_int4", "video64_bf16", "video32_bf16_f32io",
-                                  "video64_i4i4", "flux128_i4i8_f32"])
+                                  "video64_i4i4", "video64_i4i8_f32", "flux128_i4i8_f32"])
 def test_fused_entry_points_are_bit_identical_to_the_separate_steps(name):
     """paro_permute_quantize == paro_permute + paro_quantize and paro_sparse_attn_unpermuted ==
     paro_sparse_attn + paro_unpermute, bit for bit (so the oracle parity of the separate steps
