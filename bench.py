@@ -33,6 +33,9 @@ def attention_kernel_symbol(w):
     if w.block == 64 and w.d == 64 and w.bits_qk == 8:
         return ("_ZN4paro18attn_i8_w64_kernelILi%dE%sLi0EEEvNS_8AttnArgsE" % (w.bits_pv, t),
                 "paro::attn_i8_w64_kernel<%d, %s, 0>" % (w.bits_pv, tn), 1, 2)
+    if w.block == 64 and w.d == 64 and w.bits_qk == 4:
+        return ("_ZN4paro22attn_i8_w64_qk4_kernelILi%dE%sEEvNS_8AttnArgsE" % (w.bits_pv, t),
+                "paro::attn_i8_w64_qk4_kernel<%d, %s>" % (w.bits_pv, tn), 1, 2)
     if w.block == 64 and w.d == 128 and w.bits_qk == 8 and w.bits_pv == 8:
         return ("_ZN4paro18attn_i8_q16_kernelI%sEEvNS_8AttnArgsE" % t, "paro::attn_i8_q16_kernel<%s>" % tn, 4, 4)
     return ("_ZN4paro14attn_i8_kernelILi%dELi%dELi%dELi%dE%sLi0EEEvNS_8AttnArgsE" % (w.block, w.d, w.bits_qk, w.bits_pv, t),

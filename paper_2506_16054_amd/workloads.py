@@ -78,6 +78,8 @@ WORKLOADS: Dict[str, Workload] = {
 WORKLOAD_ORDER = ("tiny", "cogvideox2b", "cogvideox5b", "cogvideox5b_int4pv", "flux")
 # The unquantized 16-bit sparse mode (the sparse-only rows of the paper's Tab. 1) on the headline shape.
 WORKLOADS["cogvideox5b_bf16"] = WORKLOADS["cogvideox5b"].replace(name="cogvideox5b_bf16", bits_qk=16, bits_pv=16)
+# The all-INT4 setting of the paper's Tab. 1 ("QK (INT4), PV (INT4)") on the shape and density of the INT4-PV config.
+WORKLOADS["cogvideox5b_int4"] = WORKLOADS["cogvideox5b_int4pv"].replace(name="cogvideox5b_int4", bits_qk=4)
 
 
 # --------------------------------------------------------------------------------------------
