@@ -997,8 +997,10 @@ __device__ __forceinline__ void attn_i8_w64_body(const AttnArgs& a) {
     constexpr bool FOLDABLE = PARO_FOLD_LOGIT_BIAS && PVBITS == 8;
     bool fold = false;
     if constexpr (FOLDABLE) {  // same rule as attn_i8_kernel
-        float sk_max = 0.0f;
-        for (int base = 0; base < cnt; base += 64)
+        // the first two chunks of column indices are in registers already (a lane past the end holds the row's last column)
+        float sk_max = cnt > 0 ? skp[cols_cur] : 0.0f;
+        if (cnt > 64) sk_max = fmaxf(sk_max, skp[cols_nxt]);
+        for (int base = 128; base < cnt; base += 64)
             if (base + lane < cnt) sk_max = fmaxf(sk_max, skp[min(max(cols[base + lane], 0), a.kblocks - 1)]);
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) sk_max = fmaxf(sk_max, __shfl_xor(sk_max, off));
@@ -1195,6 +1197,18 @@ __global__ __launch_bounds__(256, 3) void attn_i8_q16_kernel(AttnArgs a) {
         }
         if (cnt > 2) j2 = col_at(2);
     }
+    constexpr bool FOLDABLE = PARO_FOLD_LOGIT_BIAS;
+    bool fold = false;
+    if constexpr (FOLDABLE) {  // same rule as attn_i8_kernel; its loads travel while the first tiles do
+        // the first two chunks of column indices are in registers already (a lane past the end holds the row's last column)
+        float sk_max = cnt > 0 ? skp[cols_cur] : 0.0f;
+        if (cnt > 64) sk_max = fmaxf(sk_max, skp[cols_nxt]);
+        for (int base = 128; base < cnt; base += 64)
+            if (base + lane < cnt) sk_max = fmaxf(sk_max, skp[min(max(cols[base + lane], 0), a.kblocks - 1)]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) sk_max = fmaxf(sk_max, __shfl_xor(sk_max, off));
+        fold = sq_i * sk_max * kAccBiasF < 8192.0f;
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
     const int tail_block = (a.n_tokens % BLK) != 0 ? a.kblocks - 1 : -1;  // the column block with padded keys, if any
@@ -1310,16 +1324,6 @@ __global__ __launch_bounds__(256, 3) void attn_i8_q16_kernel(AttnArgs a) {
         if (t + 1 < cnt) request_v(j_v, (t + 1) & 1);
     };
 
-    constexpr bool FOLDABLE = PARO_FOLD_LOGIT_BIAS;
-    bool fold = false;
-    if constexpr (FOLDABLE) {  // same rule as attn_i8_kernel
-        float sk_max = 0.0f;
-        for (int base = 0; base < cnt; base += 64)
-            if (base + lane < cnt) sk_max = fmaxf(sk_max, skp[min(max(cols[base + lane], 0), a.kblocks - 1)]);
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) sk_max = fmaxf(sk_max, __shfl_xor(sk_max, off));
-        fold = sq_i * sk_max * kAccBiasF < 8192.0f;
-    }
     PARO_TIMELINE_PHASE(4)  // everything in front of the block loop
     if (fold) {
         for (int t = 0; t < cnt; ++t) step(std::bool_constant<FOLDABLE>{}, t);
