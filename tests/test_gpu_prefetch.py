@@ -142,3 +142,4 @@ def test_prefetched_sequence_is_bit_identical_to_host_built_lists(lists_on_host)
         assert torch.equal(o, want[i % T]), "step %d (mask %d) differs from the host-built block list" % (i, i % T)
     # and at least two of the masks give different outputs, so the comparison can tell them apart
     assert not torch.equal(want[0], want[3])
+
